@@ -1,0 +1,216 @@
+"""Pins for oracle/attention.py against things other than itself: finite
+differences, PyTorch's CPU softmax / autograd, closed forms and invariants.
+Each pin is chosen so that a dropped term, a wrong sign or index or a transposed
+operand in the oracle fails at least one of them."""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+import dfa_inputs
+from oracle import attention as A
+
+
+def _np(*ts):
+    return [t.to(torch.float64).numpy() for t in ts]
+
+
+def _case(seed, h_q, h_kv, n, d):
+    return _np(*dfa_inputs.small_case(seed, h_q, h_kv, n, d))
+
+
+# ----------------------------------------------------------------- forward
+def test_softmax_rows_sum_to_one_and_causal():
+    q, k, v, do = _case(1, 4, 2, 37, 8)
+    P = A.softmax_weights(q, k, 0.3)
+    assert np.abs(P.sum(-1) - 1).max() < 1e-14
+    assert np.all(np.triu(P, 1) == 0)          # no weight on future keys
+    assert np.all(np.diagonal(P, axis1=1, axis2=2) > 0)  # a token attends to itself
+
+
+def test_row0_and_equal_keys_closed_forms():
+    q, k, v, do = _case(2, 2, 2, 33, 16)
+    scale = 0.25
+    O, L = A.attention_fwd(q, k, v, scale)
+    # row 0 sees one key: O_0 = V_0, L_0 = scale q0.k0
+    assert np.abs(O[:, 0] - v[:, 0]).max() < 1e-14
+    assert np.abs(L[:, 0] - scale * (q[:, 0] * k[:, 0]).sum(-1)).max() < 1e-13
+    # all keys equal -> uniform weights: O_i = prefix mean of V, L_i = c_i + log(i+1)
+    k2 = np.broadcast_to(k[:, :1], k.shape).copy()
+    O2, L2 = A.attention_fwd(q, k2, v, scale)
+    pref = np.cumsum(v, axis=1) / np.arange(1, 34)[None, :, None]
+    assert np.abs(O2 - pref).max() < 1e-13
+    c = scale * np.einsum("hnd,hd->hn", q, k[:, 0])
+    assert np.abs(L2 - (c + np.log(np.arange(1, 34))[None])).max() < 1e-12
+    # V constant along the sequence -> O equals that constant
+    v3 = np.broadcast_to(v[:, :1], v.shape).copy()
+    O3, _ = A.attention_fwd(q, k, v3, scale)
+    assert np.abs(O3 - v3).max() < 1e-13
+
+
+def test_key_shift_invariance():
+    q, k, v, do = _case(3, 2, 1, 29, 8)
+    scale = 0.4
+    c = np.linspace(-1, 1, 8)
+    O, L = A.attention_fwd(q, k, v, scale)
+    O2, L2 = A.attention_fwd(q, k + c, v, scale)
+    assert np.abs(O - O2).max() < 1e-12
+    assert np.abs(L2 - (L + scale * q @ c)).max() < 1e-12
+
+
+@pytest.mark.parametrize("h_q,h_kv,n,d", [(2, 2, 48, 16), (4, 1, 65, 8), (8, 2, 130, 32)])
+def test_forward_matches_torch_softmax(h_q, h_kv, n, d):
+    """Special case that is a library routine: masked softmax + matmul in torch fp64."""
+    tq, tk, tv, tdo = [t.double() for t in dfa_inputs.small_case(7, h_q, h_kv, n, d)]
+    scale = 1 / math.sqrt(d)
+    g = h_q // h_kv
+    kk = tk.repeat_interleave(g, 0); vv = tv.repeat_interleave(g, 0)
+    s = scale * tq @ kk.transpose(1, 2)
+    s = s.masked_fill(torch.triu(torch.ones(n, n, dtype=torch.bool), 1), float("-inf"))
+    ref_o = torch.softmax(s, -1) @ vv
+    ref_l = torch.logsumexp(s, -1)
+    O, L = A.attention_fwd(tq.numpy(), tk.numpy(), tv.numpy(), scale, row_block=32)
+    assert np.abs(O - ref_o.numpy()).max() < 1e-13
+    assert np.abs(L - ref_l.numpy()).max() < 1e-13
+    # and torch's fused CPU attention
+    sdpa = torch.nn.functional.scaled_dot_product_attention(
+        tq[None], kk[None], vv[None], is_causal=True, scale=scale)[0]
+    assert np.abs(O - sdpa.numpy()).max() < 1e-12
+
+
+# ---------------------------------------------------------------- backward
+def test_backward_finite_differences():
+    q, k, v, do = _case(11, 2, 1, 12, 6)
+    scale = 0.37
+
+    def loss(q_, k_, v_):
+        return float((A.attention_fwd(q_, k_, v_, scale)[0] * do).sum())
+
+    dq, dk, dv = A.attention_bwd(q, k, v, do, scale)
+    eps = 1e-6
+    rng = np.random.default_rng(0)
+    for arr, grad, idx in ((q, dq, 0), (k, dk, 1), (v, dv, 2)):
+        for _ in range(40):
+            pos = tuple(rng.integers(0, s) for s in arr.shape)
+            args = [q.copy(), k.copy(), v.copy()]
+            args[idx][pos] += eps
+            up = loss(*args)
+            args[idx][pos] -= 2 * eps
+            dn = loss(*args)
+            fd = (up - dn) / (2 * eps)
+            assert abs(fd - grad[pos]) <= 1e-7 * max(1.0, abs(fd)), (idx, pos, fd, grad[pos])
+
+
+@pytest.mark.parametrize("h_q,h_kv,n,d", [(2, 2, 40, 16), (4, 2, 67, 8)])
+def test_backward_matches_torch_autograd(h_q, h_kv, n, d):
+    tq, tk, tv, tdo = [t.double() for t in dfa_inputs.small_case(13, h_q, h_kv, n, d)]
+    scale = 1 / math.sqrt(d)
+    g = h_q // h_kv
+    tq.requires_grad_(True); tk.requires_grad_(True); tv.requires_grad_(True)
+    s = scale * tq @ tk.repeat_interleave(g, 0).transpose(1, 2)
+    s = s.masked_fill(torch.triu(torch.ones(n, n, dtype=torch.bool), 1), float("-inf"))
+    o = torch.softmax(s, -1) @ tv.repeat_interleave(g, 0)
+    o.backward(tdo)
+    dq, dk, dv = A.attention_bwd(tq.detach().numpy(), tk.detach().numpy(), tv.detach().numpy(),
+                                 tdo.numpy(), scale, row_block=16)
+    assert np.abs(dq - tq.grad.numpy()).max() < 1e-12
+    assert np.abs(dk - tk.grad.numpy()).max() < 1e-12
+    assert np.abs(dv - tv.grad.numpy()).max() < 1e-12
+
+
+def test_backward_invariants():
+    q, k, v, do = _case(17, 4, 2, 50, 8)
+    scale = 0.3
+    dq, dk, dv = A.attention_bwd(q, k, v, do, scale)
+    g = 2
+    # softmax rows sum to 1  ->  sum_j dV_j = sum_i dO_i over the group's query heads
+    assert np.abs(dv.sum(1) - do.reshape(2, g, 50, 8).sum((1, 2))).max() < 1e-12
+    # shift invariance in k  ->  sum_j dK_j = 0
+    assert np.abs(dk.sum(1)).max() < 1e-12
+    # S depends on q.k only  ->  <Q,dQ> = <K,dK>
+    assert abs((q * dq).sum() - (k * dk).sum()) < 1e-10
+    # row 0 has a single key: its softmax is constant, so dQ_0 = 0
+    assert np.abs(dq[:, 0]).max() < 1e-14
+    # V constant along the sequence -> O constant -> dQ = dK = 0
+    v3 = np.broadcast_to(v[:, :1], v.shape).copy()
+    dq3, dk3, _ = A.attention_bwd(q, k, v3, do, scale)
+    assert np.abs(dq3).max() < 1e-12 and np.abs(dk3).max() < 1e-12
+
+
+def test_delta_identity():
+    q, k, v, do = _case(19, 2, 2, 30, 8)
+    O, _ = A.attention_fwd(q, k, v, 0.5)
+    P = A.softmax_weights(q, k, 0.5)
+    dP = do @ np.swapaxes(v, 1, 2)
+    assert np.abs(A.delta_rows(O, do) - (P * dP).sum(-1)).max() < 1e-13
+
+
+# ------------------------------------------------- chunk pairs and merging
+@pytest.mark.parametrize("P", range(1, 10))
+def test_merged_pair_partials_equal_monolithic(P):
+    c, d = 6, 8
+    q, k, v, do = _case(100 + P, 4, 2, P * c, d)
+    scale = 1 / math.sqrt(d)
+    O, L = A.attention_fwd(q, k, v, scale)
+    D = A.delta_rows(O, do)
+    dQ, dK, dV = A.attention_bwd(q, k, v, do, scale)
+    aq = np.zeros_like(dQ); ak = np.zeros_like(dK); av = np.zeros_like(dV)
+    for p in range(P):
+        o_acc = np.zeros((4, c, d)); l_acc = np.full((4, c), -np.inf)
+        order = list(range(p + 1))
+        if P % 2:
+            order.reverse()            # merge order must not matter
+        for r in order:
+            o_p, l_p = A.pair_fwd(q, k, v, scale, p, r, c)
+            o_acc, l_acc = A.merge(o_acc, l_acc, o_p, l_p)
+            dq, dk, dv = A.pair_bwd(q, k, v, do, L, D, scale, p, r, c)
+            aq[:, p * c:(p + 1) * c] += dq
+            ak[:, r * c:(r + 1) * c] += dk
+            av[:, r * c:(r + 1) * c] += dv
+        assert np.abs(o_acc - O[:, p * c:(p + 1) * c]).max() < 1e-12
+        assert np.abs(l_acc - L[:, p * c:(p + 1) * c]).max() < 1e-12
+    assert np.abs(aq - dQ).max() < 1e-12
+    assert np.abs(ak - dK).max() < 1e-12
+    assert np.abs(av - dV).max() < 1e-12
+
+
+def test_merge_identity_commutative_and_two_key_closed_form():
+    rng = np.random.default_rng(5)
+    o_a = rng.normal(size=(3, 7, 4)); o_b = rng.normal(size=(3, 7, 4))
+    l_a = rng.normal(size=(3, 7)); l_b = rng.normal(size=(3, 7))
+    o0 = np.zeros_like(o_a); l0 = np.full_like(l_a, -np.inf)
+    o, l = A.merge(o0, l0, o_a, l_a)
+    assert np.array_equal(o, o_a) and np.array_equal(l, l_a)
+    o, l = A.merge(o_a, l_a, o0, l0)
+    assert np.array_equal(o, o_a) and np.array_equal(l, l_a)
+    o, l = A.merge(o0, l0, o0, l0)
+    assert not np.isnan(o).any() and np.all(np.isneginf(l))
+    o1, l1 = A.merge(o_a, l_a, o_b, l_b)
+    o2, l2 = A.merge(o_b, l_b, o_a, l_a)
+    assert np.abs(o1 - o2).max() < 1e-15 and np.abs(l1 - l2).max() < 1e-15
+    # closed form: weights are the two-way softmax of (l_a, l_b)
+    wa = 1 / (1 + np.exp(l_b - l_a))
+    assert np.abs(o1 - (wa[..., None] * o_a + (1 - wa)[..., None] * o_b)).max() < 1e-14
+    assert np.abs(l1 - np.log(np.exp(l_a) + np.exp(l_b))).max() < 1e-14
+
+
+def test_row_and_column_samplers_match_full():
+    c, P, d = 8, 4, 8
+    q, k, v, do = _case(23, 4, 2, P * c, d)
+    scale = 0.35
+    O, L = A.attention_fwd(q, k, v, scale)
+    D = A.delta_rows(O, do)
+    dQ, dK, dV = A.attention_bwd(q, k, v, do, scale)
+    rows = np.array([0, 7, 8, 19, 31])
+    h, kh = 3, 1
+    o_r, l_r = A.rows_fwd(q[h, rows], rows, k[kh], v[kh], scale)
+    assert np.abs(o_r - O[h, rows]).max() < 1e-13 and np.abs(l_r - L[h, rows]).max() < 1e-13
+    dq_r = A.rows_dq(q[h, rows], rows, do[h, rows], L[h, rows], D[h, rows], k[kh], v[kh], scale)
+    assert np.abs(dq_r - dQ[h, rows]).max() < 1e-13
+    cols = np.array([0, 5, 16, 31])
+    dk_c = np.zeros((4, d)); dv_c = np.zeros((4, d))
+    for hh in (2, 3):
+        a, b = A.cols_dkdv(k[kh, cols], v[kh, cols], cols, q[hh], do[hh], L[hh], D[hh], scale)
+        dk_c += a; dv_c += b
+    assert np.abs(dk_c - dK[kh, cols]).max() < 1e-13 and np.abs(dv_c - dV[kh, cols]).max() < 1e-13
