@@ -1,0 +1,133 @@
+"""Runs DistFlashAttn schedules on one GPU with virtual workers.
+
+Host-side sequencing only: which chunk pair is computed when comes from `dfa_schedule`
+(Section 3.2, Algorithm 2), every computation is a call into libdfa.so.  "Sending" a
+partial result to another worker is just handing over a buffer, since all P workers live
+on the same device here.
+"""
+from __future__ import annotations
+
+import torch
+
+from . import binding as B
+
+
+class Buffers:
+    """Device buffers for one run, allocated once so that timed regions allocate nothing."""
+
+    def __init__(self, h_q, h_kv, n, d, p, device, o_dtype=torch.float32, n_partials=1, grads=True):
+        c = n // p
+        self.c, self.p = c, p
+        self.O = torch.empty((h_q, n, d), dtype=o_dtype, device=device)
+        self.L = torch.empty((h_q, n), dtype=torch.float32, device=device)
+        self.part_o = [torch.empty((h_q, c, d), dtype=o_dtype, device=device) for _ in range(n_partials)]
+        self.part_l = [torch.empty((h_q, c), dtype=torch.float32, device=device) for _ in range(n_partials)]
+        if grads:
+            self.delta = torch.empty((h_q, n), dtype=torch.float32, device=device)
+            self.dQ = torch.zeros((h_q, n, d), dtype=torch.float32, device=device)
+            self.dK = torch.zeros((h_kv, n, d), dtype=torch.float32, device=device)
+            self.dV = torch.zeros((h_kv, n, d), dtype=torch.float32, device=device)
+
+
+def _chunk(t, i, c):
+    return t[:, i * c:(i + 1) * c]
+
+
+def forward_worker(Q, K, V, scale, P, w, bufs: Buffers, remote=None, mode="balanced"):
+    """Forward share of worker w: its diagonal chunk, its OWN pairs merged into (O_w, L_w),
+    the partials that arrive from helpers (`remote`: {helper_id: (o, lse)}) merged at the step
+    they arrive, and its HELP pairs computed into fresh partial buffers.
+    Returns {owner_id: (o_part, lse_part)} for the HELP pairs this worker computed."""
+    c = bufs.c
+    sent = {}
+    o_w, l_w = _chunk(bufs.O, w, c), _chunk(bufs.L, w, c)
+    for st in B.dfa_schedule(P, w, mode):
+        if st.kind == B.DFA_STEP_DIAG:
+            B.dfa_chunk_fwd(_chunk(Q, w, c), _chunk(K, w, c), _chunk(V, w, c), True, scale, o=o_w, lse=l_w)
+        elif st.kind == B.DFA_STEP_OWN:
+            po, pl = bufs.part_o[0], bufs.part_l[0]
+            B.dfa_chunk_fwd(_chunk(Q, w, c), _chunk(K, st.kv_chunk, c), _chunk(V, st.kv_chunk, c), False, scale,
+                            o=po, lse=pl)
+            B.dfa_merge(o_w, l_w, po, pl)
+        elif st.kind == B.DFA_STEP_HELP:
+            po = torch.empty_like(bufs.part_o[0]); pl = torch.empty_like(bufs.part_l[0])
+            B.dfa_chunk_fwd(_chunk(Q, st.q_chunk, c), _chunk(K, w, c), _chunk(V, w, c), False, scale, o=po, lse=pl)
+            sent[st.send_to] = (po, pl)
+        if st.recv_from >= 0 and remote is not None:
+            ro, rl = remote[st.recv_from]
+            B.dfa_merge(o_w, l_w, ro, rl)
+    return sent
+
+
+def backward_worker(Q, K, V, dO, scale, P, w, bufs: Buffers, mode="balanced", with_delta=True):
+    """Backward of the pairs worker w computed in the forward (same pair -> worker assignment),
+    from the final merged O and L of each query chunk; nothing of the forward is re-run.
+    For a HELP pair the logsumexp and D of the helped chunk must already be in `bufs`
+    (in the distributed setting they travel with that chunk's queries and dO)."""
+    c = bufs.c
+    for st in B.dfa_schedule(P, w, mode):
+        if st.kind == B.DFA_STEP_IDLE:
+            continue
+        qc, kc = st.q_chunk, st.kv_chunk
+        if with_delta and st.kind == B.DFA_STEP_DIAG:
+            B.dfa_delta(_chunk(bufs.O, qc, c), _chunk(dO, qc, c), delta=_chunk(bufs.delta, qc, c))
+        B.dfa_chunk_bwd(_chunk(Q, qc, c), _chunk(K, kc, c), _chunk(V, kc, c), _chunk(bufs.L, qc, c),
+                        _chunk(bufs.delta, qc, c), _chunk(dO, qc, c), _chunk(bufs.dQ, qc, c),
+                        _chunk(bufs.dK, kc, c), _chunk(bufs.dV, kc, c), st.kind == B.DFA_STEP_DIAG, scale,
+                        accumulate=True)
+
+
+def run_worker_share(Q, K, V, dO, scale, P, w, bufs: Buffers, remote):
+    """One pass of worker w's whole share: forward (incl. merges of the helpers' partials),
+    the D pre-pass and the backward of the same pairs.  Gradient buffers are accumulated into
+    (callers zero them when they need the share's own sums)."""
+    forward_worker(Q, K, V, scale, P, w, bufs, remote=remote)
+    backward_worker(Q, K, V, dO, scale, P, w, bufs)
+
+
+def helper_partials_for(Q, K, V, scale, P, w, bufs: Buffers):
+    """The partial results other workers compute for worker w's queries under the balanced
+    schedule (what arrives over the network in the distributed setting)."""
+    c = bufs.c
+    out = {}
+    for st in B.dfa_schedule(P, w):
+        if st.recv_from >= 0:
+            h = st.recv_from
+            po = torch.empty_like(bufs.part_o[0]); pl = torch.empty_like(bufs.part_l[0])
+            B.dfa_chunk_fwd(_chunk(Q, w, c), _chunk(K, h, c), _chunk(V, h, c), False, scale, o=po, lse=pl)
+            out[h] = (po, pl)
+    return out
+
+
+def run_all_workers(Q, K, V, dO, scale, P, bufs: Buffers, mode="balanced", backward=True):
+    """The whole schedule of all P workers, time step by time step, on one GPU."""
+    c = bufs.c
+    scheds = [B.dfa_schedule(P, w, mode) for w in range(P)]
+    nsteps = len(scheds[0])
+    for t in range(nsteps):
+        arrivals = []
+        for w in range(P):
+            st = scheds[w][t]
+            if st.kind == B.DFA_STEP_DIAG:
+                B.dfa_chunk_fwd(_chunk(Q, w, c), _chunk(K, w, c), _chunk(V, w, c), True, scale,
+                                o=_chunk(bufs.O, w, c), lse=_chunk(bufs.L, w, c))
+            elif st.kind == B.DFA_STEP_OWN:
+                po, pl = bufs.part_o[0], bufs.part_l[0]
+                B.dfa_chunk_fwd(_chunk(Q, w, c), _chunk(K, st.kv_chunk, c), _chunk(V, st.kv_chunk, c), False,
+                                scale, o=po, lse=pl)
+                B.dfa_merge(_chunk(bufs.O, w, c), _chunk(bufs.L, w, c), po, pl)
+            elif st.kind == B.DFA_STEP_HELP:
+                po, pl = bufs.part_o[0], bufs.part_l[0]
+                B.dfa_chunk_fwd(_chunk(Q, st.q_chunk, c), _chunk(K, w, c), _chunk(V, w, c), False, scale,
+                                o=po, lse=pl)
+                # "send": the owner merges it in this same step
+                B.dfa_merge(_chunk(bufs.O, st.send_to, c), _chunk(bufs.L, st.send_to, c), po, pl)
+                arrivals.append((st.send_to, w))
+        for owner, helper in arrivals:
+            assert scheds[owner][t].recv_from == helper
+    if backward:
+        # a helper's backward needs D of the chunk it helped, so all D vectors come first
+        for w in range(P):
+            B.dfa_delta(_chunk(bufs.O, w, c), _chunk(dO, w, c), delta=_chunk(bufs.delta, w, c))
+        for w in range(P):
+            backward_worker(Q, K, V, dO, scale, P, w, bufs, mode, with_delta=False)

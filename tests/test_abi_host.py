@@ -1,0 +1,112 @@
+"""CPU-only checks of the C-ABI library: it loads, exports every function the header
+declares, validates arguments on the host (no launch on error), and its schedule equals
+the oracle's enumerator."""
+import ctypes
+import os
+import re
+
+import pytest
+
+import paper_2310_03294_amd as dfa
+from paper_2310_03294_amd import binding as B
+from oracle import schedule as S
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(dfa.lib_path()):
+        import __graft_entry__ as g
+        g.build()
+    return dfa.load_library()
+
+
+def test_exports_every_declared_symbol(lib):
+    hdr = open(os.path.join(ROOT, "include", "dfa.h")).read()
+    hdr = re.sub(r"/\*.*?\*/", "", hdr, flags=re.S)
+    names = set(re.findall(r"\b(dfa_[a-z_]+)\s*\(", hdr))
+    assert {"dfa_chunk_fwd", "dfa_merge", "dfa_chunk_bwd", "dfa_schedule", "dfa_delta"} <= names
+    for n in names:
+        assert hasattr(lib, n), n
+    assert set(B.EXPORTS) == names
+    assert lib.dfa_version() >= 100
+
+
+def test_shape_struct_matches_header():
+    # 10 32-bit fields then 11 64-bit strides
+    assert ctypes.sizeof(B.DfaShape) == 10 * 4 + 11 * 8
+    assert ctypes.sizeof(B.DfaStep) == 24
+
+
+@pytest.mark.parametrize("P", list(range(1, 34)) + [64])
+def test_schedule_matches_oracle(lib, P):
+    for mode, ref in (("balanced", S.balanced(P)), ("ring", S.ring(P))):
+        for w in range(P):
+            got = dfa.dfa_schedule(P, w, mode)
+            want = ref[w]
+            assert len(got) == len(want)
+            for g, r in zip(got, want):
+                assert g._asdict() == r
+
+
+def test_schedule_errors_and_cap(lib):
+    buf = (B.DfaStep * 2)()
+    assert lib.dfa_schedule(0, 0, buf, 2) == -4
+    assert lib.dfa_schedule(4, 4, buf, 2) == -4
+    assert lib.dfa_schedule(4, -1, buf, 2) == -4
+    assert lib.dfa_schedule(4, 0, None, 2) == -1
+    assert lib.dfa_schedule(8, 7, buf, 2) == 5          # truncated write, full count returned
+    assert buf[1].kind == B.DFA_STEP_OWN and buf[1].kv_chunk == 6 and buf[1].recv_from == 0
+    assert lib.dfa_schedule(8, 7, None, 0) == 5
+    assert lib.dfa_schedule_mode(7, 8, 0, buf, 2) == -4
+
+
+def _shape(**kw):
+    sh = B.DfaShape()
+    base = dict(h_q=2, h_kv=2, s_q=64, s_k=64, d=64, dtype=B.DFA_F32, o_dtype=B.DFA_F32, causal=0, scale=0.125,
+                reserved=0, q_stride_h=64 * 64, q_stride_s=64, kv_stride_h=64 * 64, kv_stride_s=64,
+                o_stride_h=64 * 64, o_stride_s=64, lse_stride_h=64, dq_stride_h=64 * 64, dq_stride_s=64,
+                dkv_stride_h=64 * 64, dkv_stride_s=64)
+    base.update(kw)
+    for k, v in base.items():
+        setattr(sh, k, v)
+    return sh
+
+
+FAKE = 4096  # non-null, 16-byte aligned, never dereferenced: validation fails before any launch
+
+
+@pytest.mark.parametrize("kw,code", [
+    (dict(d=96), -2), (dict(h_q=3, h_kv=2), -2), (dict(s_q=-1), -2), (dict(dtype=5), -3), (dict(o_dtype=9), -3),
+    (dict(causal=1, s_k=128), -4), (dict(causal=2), -4), (dict(scale=0.0), -4), (dict(scale=float("nan")), -4),
+    (dict(reserved=1), -4), (dict(q_stride_s=60), -2), (dict(kv_stride_s=63), -2), (dict(o_stride_h=12), -2),
+    (dict(lse_stride_h=32), -2), (dict(dtype=B.DFA_BF16, d=64), -2),
+])
+def test_fwd_argument_errors(lib, kw, code):
+    sh = _shape(**kw)
+    assert lib.dfa_chunk_fwd(ctypes.byref(sh), FAKE, FAKE, FAKE, FAKE, FAKE, None) == code
+    assert code < 0 and dfa.dfa_status_str(code) != "unknown dfa_status"
+
+
+def test_null_and_alignment_errors(lib):
+    sh = _shape()
+    assert lib.dfa_chunk_fwd(None, FAKE, FAKE, FAKE, FAKE, FAKE, None) == -1
+    assert lib.dfa_chunk_fwd(ctypes.byref(sh), None, FAKE, FAKE, FAKE, FAKE, None) == -1
+    assert lib.dfa_chunk_fwd(ctypes.byref(sh), FAKE + 4, FAKE, FAKE, FAKE, FAKE, None) == -2
+    assert lib.dfa_chunk_bwd(ctypes.byref(sh), FAKE, FAKE, FAKE, FAKE, None, FAKE, FAKE, FAKE, FAKE, 0, None) == -1
+    assert lib.dfa_chunk_bwd(ctypes.byref(_shape(dq_stride_s=8)), FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE,
+                             FAKE, 0, None) == -2
+    assert lib.dfa_delta(ctypes.byref(sh), FAKE, None, FAKE, None) == -1
+    assert lib.dfa_merge(-1, 64, B.DFA_F32, FAKE, 64, FAKE, FAKE * 2, 64, FAKE * 2, None) == -2
+    assert lib.dfa_merge(8, 48, B.DFA_F32, FAKE, 64, FAKE, FAKE * 2, 64, FAKE * 2, None) == -2
+    assert lib.dfa_merge(8, 64, 7, FAKE, 64, FAKE, FAKE * 2, 64, FAKE * 2, None) == -3
+    assert lib.dfa_merge(8, 64, B.DFA_F32, FAKE, 64, FAKE, FAKE, 64, FAKE * 2, None) == -4   # aliasing
+    assert lib.dfa_merge(8, 64, B.DFA_F32, None, 64, FAKE, FAKE * 2, 64, FAKE * 2, None) == -1
+    assert lib.dfa_merge(0, 64, B.DFA_F32, FAKE, 64, FAKE, FAKE * 2, 64, FAKE * 2, None) == 0   # empty: no-op
+
+
+def test_empty_query_chunk_is_noop(lib):
+    sh = _shape(s_q=0, lse_stride_h=0)
+    assert lib.dfa_chunk_fwd(ctypes.byref(sh), FAKE, FAKE, FAKE, FAKE, FAKE, None) == 0
+    assert lib.dfa_delta(ctypes.byref(sh), FAKE, FAKE, FAKE, None) == 0

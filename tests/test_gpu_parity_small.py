@@ -1,0 +1,183 @@
+"""GPU parity, element by element against the fp64 oracle, at sizes the oracle finishes in
+seconds: the merge, the D pre-pass, single chunk pairs (square, ragged, GQA, causal and
+not), empty inputs, and whole balanced schedules incl. config 1."""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+import dfa_inputs
+import paper_2310_03294_amd as dfa
+from paper_2310_03294_amd import driver
+from oracle import attention as A
+from gpu_util import TOL, case, dev, maxerr, np64
+
+pytestmark = pytest.mark.gpu
+
+
+def _single_pair_oracle(q, k, v, do, scale, causal):
+    """Oracle for ONE pair used as a whole problem (final lse == the pair's lse)."""
+    q64, k64, v64, do64 = (np64(t) for t in (q, k, v, do))
+    h_q, s_q, d = q64.shape
+    h_kv, s_k = k64.shape[:2]
+    g = h_q // h_kv
+    O = np.empty_like(q64); L = np.empty((h_q, s_q))
+    dq = np.empty_like(q64); dk = np.zeros_like(k64); dv = np.zeros_like(v64)
+    for h in range(h_q):
+        kh = h // g
+        s = scale * q64[h] @ k64[kh].T
+        if causal:
+            s = np.where(np.arange(s_k)[None, :] <= np.arange(s_q)[:, None], s, -np.inf)
+        m = s.max(1, keepdims=True)
+        e = np.exp(s - m); l = e.sum(1, keepdims=True); p = e / l
+        O[h] = p @ v64[kh]; L[h] = (m + np.log(l))[:, 0]
+        dp = do64[h] @ v64[kh].T
+        ds = p * (dp - (p * dp).sum(1, keepdims=True))
+        dq[h] = scale * ds @ k64[kh]; dk[kh] += scale * ds.T @ q64[h]; dv[kh] += p.T @ do64[h]
+    return O, L, dq, dk, dv
+
+
+def test_single_pair_oracle_helper_agrees_with_oracle_module():
+    # the helper above handles s_q != s_k; on square causal input it must equal the oracle proper
+    q, k, v, do = case(5, 4, 2, 48, 48, 16, torch.float32)
+    O, L, dq, dk, dv = _single_pair_oracle(q, k, v, do, 0.25, True)
+    O2, L2 = A.attention_fwd(np64(q), np64(k), np64(v), 0.25)
+    g = A.attention_bwd(np64(q), np64(k), np64(v), np64(do), 0.25)
+    for a, b in ((O, O2), (L, L2), (dq, g[0]), (dk, g[1]), (dv, g[2])):
+        assert np.abs(a - b).max() < 1e-12
+
+
+SHAPES_F32 = [
+    # h_q, h_kv, s_q, s_k, d, causal
+    (1, 1, 256, 256, 64, True), (2, 2, 64, 64, 128, False), (4, 2, 130, 130, 64, True),
+    (3, 1, 100, 77, 128, False), (2, 1, 1, 1, 64, True), (2, 2, 65, 191, 64, False), (8, 2, 257, 257, 128, True),
+]
+SHAPES_BF16 = [
+    (2, 2, 128, 128, 128, True), (2, 2, 256, 192, 128, False), (4, 2, 384, 384, 128, True),
+    (3, 1, 100, 77, 128, False), (2, 1, 1, 1, 128, True), (2, 2, 65, 191, 128, False), (8, 2, 257, 257, 128, True),
+    (1, 1, 1024, 1024, 128, True), (2, 1, 640, 1152, 128, False),
+]
+
+
+def _run_pair(dtype, h_q, h_kv, s_q, s_k, d, causal, o_dtype=torch.float32):
+    q, k, v, do = case(1000 + s_q + s_k, h_q, h_kv, s_q, s_k, d, dtype)
+    scale = 1 / math.sqrt(d)
+    Q, K, V, dO = (t.to(dev()) for t in (q, k, v, do))
+    o, lse = dfa.dfa_chunk_fwd(Q, K, V, causal, scale, o_dtype=o_dtype)
+    delta = dfa.dfa_delta(o, dO)
+    dq = torch.full((h_q, s_q, d), 7.0, device=dev()); dk = torch.full((h_kv, s_k, d), 7.0, device=dev())
+    dv = torch.full((h_kv, s_k, d), 7.0, device=dev())
+    dfa.dfa_chunk_bwd(Q, K, V, lse, delta, dO, dq, dk, dv, causal, scale, accumulate=False)
+    torch.cuda.synchronize()
+    O, L, rq, rk, rv = _single_pair_oracle(q, k, v, do, scale, causal)
+    tol = TOL[dtype]
+    errs = dict(o=maxerr(o, O), lse=maxerr(lse, L), dq=maxerr(dq, rq), dk=maxerr(dk, rk), dv=maxerr(dv, rv),
+                delta=maxerr(delta, (O * np64(do)).sum(-1)))
+    assert all(e <= tol for e in errs.values()), errs
+    # accumulate != 0 adds the same contribution on top
+    dfa.dfa_chunk_bwd(Q, K, V, lse, delta, dO, dq, dk, dv, causal, scale, accumulate=True)
+    torch.cuda.synchronize()
+    errs2 = dict(dq=maxerr(dq, 2 * rq), dk=maxerr(dk, 2 * rk), dv=maxerr(dv, 2 * rv))
+    assert all(e <= 2 * tol for e in errs2.values()), errs2
+
+
+@pytest.mark.parametrize("shape", SHAPES_F32)
+def test_pair_f32(shape):
+    _run_pair(torch.float32, *shape)
+
+
+@pytest.mark.parametrize("shape", SHAPES_BF16)
+def test_pair_bf16(shape):
+    _run_pair(torch.bfloat16, *shape)
+
+
+def test_pair_bf16_output_dtype_bf16():
+    _run_pair(torch.bfloat16, 2, 2, 256, 256, 128, True, o_dtype=torch.bfloat16)
+
+
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+@pytest.mark.parametrize("d", [64, 128])
+def test_merge(dtype, d):
+    rows_h, rows_s = 3, 1000
+    g = torch.Generator().manual_seed(3)
+    o_a = torch.randn(rows_h, rows_s, d, generator=g).to(dtype); o_b = torch.randn(rows_h, rows_s, d, generator=g).to(dtype)
+    l_a = 3 * torch.randn(rows_h, rows_s, generator=g); l_b = 3 * torch.randn(rows_h, rows_s, generator=g)
+    # identities and degenerate rows
+    l_a[0, :10] = -math.inf; o_a[0, :10] = 0
+    l_b[0, 5:20] = -math.inf; o_b[0, 5:20] = 0
+    l_a[1, 0] = 80.0; l_b[1, 0] = -80.0
+    want_o, want_l = A.merge(np64(o_a), np64(l_a), np64(o_b), np64(l_b))
+    A_, LA = o_a.to(dev()), l_a.to(dev())
+    dfa.dfa_merge(A_, LA, o_b.to(dev()), l_b.to(dev()))
+    torch.cuda.synchronize()
+    got_o, got_l = np64(A_), np64(LA)
+    assert not np.isnan(got_o).any() and not np.isnan(got_l).any()
+    fin = np.isfinite(want_l)
+    assert np.array_equal(np.isneginf(got_l), np.isneginf(want_l))
+    assert np.abs(got_l[fin] - want_l[fin]).max() <= 1e-5
+    assert np.abs(got_o - want_o).max() <= TOL[dtype]
+    assert np.all(got_o[0, 5:10] == 0)
+
+
+def test_merge_strided_rows():
+    d = 128
+    big = torch.randn(2, 64, 2 * d).to(dev())
+    o_a = big[:, :, :d]          # row stride 2d
+    o_b = torch.randn(2, 64, d).to(dev())
+    l_a = torch.randn(2, 64).to(dev()); l_b = torch.randn(2, 64).to(dev())
+    want_o, want_l = A.merge(np64(o_a), np64(l_a), np64(o_b), np64(l_b))
+    keep = big[:, :, d:].clone()
+    dfa.dfa_merge(o_a, l_a, o_b, l_b)
+    torch.cuda.synchronize()
+    assert maxerr(o_a, want_o) <= 1e-5 and maxerr(l_a, want_l) <= 1e-5
+    assert torch.equal(big[:, :, d:], keep)      # neighbours untouched
+
+
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+def test_empty_key_chunk_gives_merge_identity(dtype):
+    d = 128
+    q = torch.randn(2, 96, d).to(dtype).to(dev())
+    k = torch.empty(2, 0, d, dtype=dtype, device=dev())
+    o, lse = dfa.dfa_chunk_fwd(q, k, k, False, 0.1)
+    torch.cuda.synchronize()
+    assert torch.all(o == 0) and torch.all(torch.isneginf(lse))
+    # merging it into a real partial changes nothing
+    k2 = torch.randn(2, 64, d).to(dtype).to(dev())
+    o2, l2 = dfa.dfa_chunk_fwd(q, k2, k2, False, 0.1)
+    ref_o, ref_l = o2.clone(), l2.clone()
+    dfa.dfa_merge(o2, l2, o, lse)
+    torch.cuda.synchronize()
+    assert torch.equal(o2, ref_o) and torch.equal(l2, ref_l)
+
+
+def _schedule_case(w: dfa_inputs.Workload, mode="balanced"):
+    q, k, v, do = (dfa_inputs.full_sequence(w, t) for t in range(4))
+    Q, K, V, dO = (t.to(dev()) for t in (q, k, v, do))
+    bufs = driver.Buffers(w.h_q, w.h_kv, w.n_total, w.d, w.p, dev())
+    driver.run_all_workers(Q, K, V, dO, w.scale, w.p, bufs, mode=mode)
+    torch.cuda.synchronize()
+    q64, k64, v64, do64 = (np64(t) for t in (q, k, v, do))
+    O, L = A.attention_fwd(q64, k64, v64, w.scale)
+    dQ, dK, dV = A.attention_bwd(q64, k64, v64, do64, w.scale)
+    tol = TOL[w.torch_dtype]
+    errs = dict(o=maxerr(bufs.O, O), lse=maxerr(bufs.L, L), dq=maxerr(bufs.dQ, dQ), dk=maxerr(bufs.dK, dK),
+                dv=maxerr(bufs.dV, dV))
+    assert all(e <= tol for e in errs.values()), errs
+    return errs
+
+
+def test_config1_full_balanced_schedule():
+    """Config 1: fp32, 1 head, d=64, N=1024, P=4; merged outputs of the whole schedule vs the monolithic oracle."""
+    _schedule_case(dfa_inputs.CONFIGS[0])
+
+
+def test_config1_ring_schedule():
+    _schedule_case(dfa_inputs.CONFIGS[0], mode="ring")
+
+
+@pytest.mark.parametrize("P", [1, 2, 3, 5, 8])
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_balanced_schedule_odd_even_gqa(P, dtype):
+    w = dfa_inputs.Workload(f"t_p{P}", 4, 2, 128, 192 * P, P, dtype, 4321 + P)
+    _schedule_case(w)
