@@ -88,12 +88,17 @@ int dfa_chunk_fwd(const dfa_shape* sh, const void* q, const void* k, const void*
  * Algorithm 2): exact combination of two partial results for the same query rows,
  *   lse = log(e^lse_a + e^lse_b),  o = e^(lse_a-lse) o_a + e^(lse_b-lse) o_b,
  * written IN PLACE over (o_a, lse_a).  (o = 0, lse = -inf) is the identity and never
- * produces NaN.  rows = number of (head, query) rows; o_a/o_b rows are d wide with row
- * stride o_a_stride / o_b_stride elements; o_dtype is the dtype of both o operands.
+ * produces NaN.  Operands are [heads, rows, d] (o) and [heads, rows] (lse); strides in
+ * elements, innermost stride 1; o_dtype is the dtype of both o operands.
  */
-int dfa_merge(int64_t rows, int32_t d, int32_t o_dtype,
-              void* o_a, int64_t o_a_stride, float* lse_a,
-              const void* o_b, int64_t o_b_stride, const float* lse_b, void* stream);
+typedef struct {
+  int32_t heads, rows, d, o_dtype;
+  int64_t a_stride_h, a_stride_s, lse_a_stride_h;   /* o_a, lse_a (read and written) */
+  int64_t b_stride_h, b_stride_s, lse_b_stride_h;   /* o_b, lse_b (read only) */
+} dfa_merge_desc;
+
+int dfa_merge(const dfa_merge_desc* md, void* o_a, float* lse_a,
+              const void* o_b, const float* lse_b, void* stream);
 
 /*
  * dfa_delta - D_i = sum_c dO_ic * O_ic for every query row, from the FINAL merged

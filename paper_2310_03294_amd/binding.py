@@ -37,6 +37,13 @@ class DfaShape(ctypes.Structure):
     ]
 
 
+class DfaMergeDesc(ctypes.Structure):
+    _fields_ = [("heads", ctypes.c_int32), ("rows", ctypes.c_int32), ("d", ctypes.c_int32),
+                ("o_dtype", ctypes.c_int32),
+                ("a_stride_h", ctypes.c_int64), ("a_stride_s", ctypes.c_int64), ("lse_a_stride_h", ctypes.c_int64),
+                ("b_stride_h", ctypes.c_int64), ("b_stride_s", ctypes.c_int64), ("lse_b_stride_h", ctypes.c_int64)]
+
+
 class DfaStep(ctypes.Structure):
     _fields_ = [("t", ctypes.c_int32), ("kind", ctypes.c_int32), ("q_chunk", ctypes.c_int32),
                 ("kv_chunk", ctypes.c_int32), ("send_to", ctypes.c_int32), ("recv_from", ctypes.c_int32)]
@@ -65,7 +72,7 @@ def load_library():
     vp, i32, i64 = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64
     shp = ctypes.POINTER(DfaShape)
     lib.dfa_chunk_fwd.argtypes = [shp, vp, vp, vp, vp, vp, vp]
-    lib.dfa_merge.argtypes = [i64, i32, i32, vp, i64, vp, vp, i64, vp, vp]
+    lib.dfa_merge.argtypes = [ctypes.POINTER(DfaMergeDesc), vp, vp, vp, vp, vp]
     lib.dfa_delta.argtypes = [shp, vp, vp, vp, vp]
     lib.dfa_chunk_bwd.argtypes = [shp, vp, vp, vp, vp, vp, vp, vp, vp, vp, ctypes.c_int, vp]
     lib.dfa_schedule.argtypes = [i32, i32, ctypes.POINTER(DfaStep), i32]
@@ -159,14 +166,16 @@ def dfa_merge(o_a, lse_a, o_b, lse_b, stream=None):
     lib = load_library()
     if o_a.shape != o_b.shape or lse_a.shape != lse_b.shape or o_a.dtype != o_b.dtype:
         raise ValueError("merge operands must match")
-    h, s, d = o_a.shape
-    for t, l in ((o_a, lse_a), (o_b, lse_b)):
-        if h > 1 and (t.stride(0) != s * t.stride(1) or not l.is_contiguous()):
-            raise ValueError("merge operands must be row-regular ([heads*seq] rows of one stride)")
-        if t.stride(2) != 1:
-            raise ValueError("unit innermost stride required")
-    _check(lib.dfa_merge(h * s, d, _dt(o_a), o_a.data_ptr(), o_a.stride(1), lse_a.data_ptr(),
-                         o_b.data_ptr(), o_b.stride(1), lse_b.data_ptr(), _stream(stream)), "dfa_merge")
+    md = DfaMergeDesc()
+    md.heads, md.rows, md.d = o_a.shape
+    md.o_dtype = _dt(o_a)
+    md.a_stride_h, md.a_stride_s = _hsd(o_a, "o_a")
+    md.b_stride_h, md.b_stride_s = _hsd(o_b, "o_b")
+    if lse_a.stride(1) != 1 or lse_b.stride(1) != 1:
+        raise ValueError("lse must have unit innermost stride")
+    md.lse_a_stride_h, md.lse_b_stride_h = lse_a.stride(0), lse_b.stride(0)
+    _check(lib.dfa_merge(ctypes.byref(md), o_a.data_ptr(), lse_a.data_ptr(), o_b.data_ptr(), lse_b.data_ptr(),
+                         _stream(stream)), "dfa_merge")
 
 
 def dfa_delta(o, dO, delta=None, stream=None):

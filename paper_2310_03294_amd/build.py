@@ -18,7 +18,8 @@ SOURCES = (
     "dfa_schedule.cpp",
     "dfa_elementwise.hip",
     "dfa_attn_f32.hip",
-    "dfa_attn_bf16_stub.hip",
+    "dfa_fwd_bf16.hip",
+    "dfa_bwd_bf16.hip",
 )
 
 HIP_FLAGS = (

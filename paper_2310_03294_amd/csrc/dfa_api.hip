@@ -67,17 +67,21 @@ extern "C" int dfa_chunk_fwd(const dfa_shape* sh, const void* q, const void* k, 
   return dfa::launch_fwd_bf16(*sh, q, k, v, o, lse, st);
 }
 
-extern "C" int dfa_merge(int64_t rows, int32_t d, int32_t o_dtype, void* o_a, int64_t sa, float* lse_a,
-                         const void* o_b, int64_t sb, const float* lse_b, void* stream) {
-  if (rows < 0) return DFA_ERR_SHAPE;
-  if (d != 64 && d != 128) return DFA_ERR_SHAPE;
-  if (o_dtype != DFA_BF16 && o_dtype != DFA_F32) return DFA_ERR_DTYPE;
+extern "C" int dfa_merge(const dfa_merge_desc* md, void* o_a, float* lse_a,
+                         const void* o_b, const float* lse_b, void* stream) {
+  if (!md) return DFA_ERR_NULL;
+  if (md->heads < 0 || md->rows < 0 || md->heads > 65535) return DFA_ERR_SHAPE;
+  if (md->d != 64 && md->d != 128) return DFA_ERR_SHAPE;
+  if (md->o_dtype != DFA_BF16 && md->o_dtype != DFA_F32) return DFA_ERR_DTYPE;
   if (!o_a || !lse_a || !o_b || !lse_b) return DFA_ERR_NULL;
   if (!aligned16(o_a) || !aligned16(o_b)) return DFA_ERR_SHAPE;
-  if (sa < d || sb < d || !mult8(sa) || !mult8(sb)) return DFA_ERR_SHAPE;
+  if (!stride_ok(md->a_stride_h, md->a_stride_s, md->d, md->rows) ||
+      !stride_ok(md->b_stride_h, md->b_stride_s, md->d, md->rows))
+    return DFA_ERR_SHAPE;
+  if (md->lse_a_stride_h < md->rows || md->lse_b_stride_h < md->rows) return DFA_ERR_SHAPE;
   if (o_a == o_b || lse_a == lse_b) return DFA_ERR_ARG;
-  if (rows == 0) return DFA_OK;
-  return dfa::launch_merge(rows, d, o_dtype, o_a, sa, lse_a, o_b, sb, lse_b, static_cast<hipStream_t>(stream));
+  if (md->rows == 0 || md->heads == 0) return DFA_OK;
+  return dfa::launch_merge(*md, o_a, lse_a, o_b, lse_b, static_cast<hipStream_t>(stream));
 }
 
 extern "C" int dfa_delta(const dfa_shape* sh, const void* o, const void* dO, float* delta, void* stream) {

@@ -44,16 +44,17 @@ __device__ inline void store8(void* base, int64_t elem_off, const Vec8& r) {
 
 // (o_a, lse_a) <- merge((o_a, lse_a), (o_b, lse_b)), Section 3.2 rescale(.)
 template <int D, bool BF16>
-__global__ void __launch_bounds__(256) k_merge(int64_t rows, void* __restrict__ o_a, int64_t sa,
-                                               float* __restrict__ lse_a, const void* __restrict__ o_b,
-                                               int64_t sb, const float* __restrict__ lse_b) {
+__global__ void __launch_bounds__(256) k_merge(dfa_merge_desc md, void* __restrict__ o_a, float* __restrict__ lse_a,
+                                               const void* __restrict__ o_b, const float* __restrict__ lse_b) {
   constexpr int LPR = D / 8;           // lanes per row
   constexpr int RPB = 256 / LPR;       // rows per block iteration
   const int lane = threadIdx.x % LPR;
   const int rib = threadIdx.x / LPR;
-  for (int64_t row = static_cast<int64_t>(blockIdx.x) * RPB + rib; row < rows;
-       row += static_cast<int64_t>(gridDim.x) * RPB) {
-    const float la = lse_a[row], lb = lse_b[row];
+  const int h = blockIdx.y;
+  float* la_p = lse_a + h * md.lse_a_stride_h;
+  const float* lb_p = lse_b + h * md.lse_b_stride_h;
+  for (int row = blockIdx.x * RPB + rib; row < md.rows; row += gridDim.x * RPB) {
+    const float la = la_p[row], lb = lb_p[row];
     const float m = fmaxf(la, lb);
     float wa = 0.f, wb = 0.f, l = -INFINITY;
     if (m > -INFINITY) {
@@ -63,13 +64,15 @@ __global__ void __launch_bounds__(256) k_merge(int64_t rows, void* __restrict__ 
       const float inv = 1.f / s;
       wa = ea * inv; wb = eb * inv;
     }
-    const Vec8 a = load8<BF16>(o_a, row * sa + lane * 8);
-    const Vec8 b = load8<BF16>(o_b, row * sb + lane * 8);
+    const int64_t offa = h * md.a_stride_h + static_cast<int64_t>(row) * md.a_stride_s + lane * 8;
+    const int64_t offb = h * md.b_stride_h + static_cast<int64_t>(row) * md.b_stride_s + lane * 8;
+    const Vec8 a = load8<BF16>(o_a, offa);
+    const Vec8 b = load8<BF16>(o_b, offb);
     Vec8 r;
 #pragma unroll
     for (int i = 0; i < 8; ++i) r.v[i] = wa * a.v[i] + wb * b.v[i];
-    store8<BF16>(o_a, row * sa + lane * 8, r);
-    if (lane == 0) lse_a[row] = l;
+    store8<BF16>(o_a, offa, r);
+    if (lane == 0) la_p[row] = l;
   }
 }
 
@@ -126,16 +129,19 @@ int grid_for(int64_t items, int per_block) {
 
 }  // namespace
 
-int launch_merge(int64_t rows, int d, int o_dtype, void* o_a, int64_t sa, float* lse_a,
-                 const void* o_b, int64_t sb, const float* lse_b, hipStream_t st) {
-  const int rpb = 256 / (d / 8);
-  const int grid = grid_for(rows, rpb);
-  if (d == 128) {
-    if (o_dtype == DFA_BF16) k_merge<128, true><<<grid, 256, 0, st>>>(rows, o_a, sa, lse_a, o_b, sb, lse_b);
-    else k_merge<128, false><<<grid, 256, 0, st>>>(rows, o_a, sa, lse_a, o_b, sb, lse_b);
+int launch_merge(const dfa_merge_desc& md, void* o_a, float* lse_a, const void* o_b, const float* lse_b,
+                 hipStream_t st) {
+  const int rpb = 256 / (md.d / 8);
+  int gx = (md.rows + rpb - 1) / rpb;
+  const int cap = (256 * 16 + md.heads - 1) / md.heads;   // a few blocks per CU in total; rows are grid-strided
+  if (gx > cap) gx = cap;
+  dim3 grid(gx < 1 ? 1 : gx, md.heads);
+  if (md.d == 128) {
+    if (md.o_dtype == DFA_BF16) k_merge<128, true><<<grid, 256, 0, st>>>(md, o_a, lse_a, o_b, lse_b);
+    else k_merge<128, false><<<grid, 256, 0, st>>>(md, o_a, lse_a, o_b, lse_b);
   } else {
-    if (o_dtype == DFA_BF16) k_merge<64, true><<<grid, 256, 0, st>>>(rows, o_a, sa, lse_a, o_b, sb, lse_b);
-    else k_merge<64, false><<<grid, 256, 0, st>>>(rows, o_a, sa, lse_a, o_b, sb, lse_b);
+    if (md.o_dtype == DFA_BF16) k_merge<64, true><<<grid, 256, 0, st>>>(md, o_a, lse_a, o_b, lse_b);
+    else k_merge<64, false><<<grid, 256, 0, st>>>(md, o_a, lse_a, o_b, lse_b);
   }
   return last_launch_status();
 }

@@ -1,0 +1,234 @@
+// bf16 forward chunk kernel for gfx950: attn(q_p, k_r, v_r) of one chunk pair from the empty
+// state (forward pseudo-code of Appendix A; Eq. 1 restricted to one key/value chunk).
+//
+// Work decomposition.  A workgroup of 4 wavefronts owns 128 query rows of one head, each
+// wavefront 32 of them, and walks over the key/value chunk in tiles of 64 rows staged in LDS.
+// Per tile a wavefront computes S^T = K Q^T (keys x queries) so that every lane holds 32
+// scores of ONE query: the running row maximum / row sum of the online softmax are then
+// per-lane scalars plus one exchange between lane l and l+32.  The exponentiated tile is fed
+// straight back, from registers, as the B operand of O^T += V^T P^T.
+// Q stays in registers for the whole kernel; K is read from LDS with ds_read_b128, V with the
+// transposing ds_read_b64_tr_b16.  The causal mask is applied only on tiles that straddle the
+// diagonal; tiles above it are skipped.
+#include "dfa_internal.h"
+#include "dfa_mfma.h"
+
+namespace dfa {
+namespace {
+
+constexpr int D = 128;
+constexpr int BM = 128;     // query rows per workgroup
+constexpr int BN = 64;      // key rows per LDS tile
+constexpr int NTHREADS = 256;
+constexpr int TILE_BYTES = BN * D * 2;
+constexpr float LOG2E = 1.4426950408889634f;
+
+struct FwdParams {
+  const __bf16 *q, *k, *v;
+  void* o; float* lse;
+  int s_q, s_k, h_q, group, causal, o_bf16, ntq, total, per_xcd;
+  float scale;
+  int64_t q_sh, q_ss, kv_sh, kv_ss, o_sh, o_ss, l_sh;
+};
+
+struct TileRegs { uint4 k[4], v[4]; };
+
+__device__ __forceinline__ void tile_load(TileRegs& t, const __bf16* kg, const __bf16* vg, int64_t ss,
+                                          int k0, int s_k, int tid) {
+  const int c = tid & 15;
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const int r = (tid >> 4) + 16 * i;
+    if (k0 + r < s_k) {
+      const int64_t off = static_cast<int64_t>(k0 + r) * ss + c * 8;
+      t.k[i] = *reinterpret_cast<const uint4*>(kg + off);
+      t.v[i] = *reinterpret_cast<const uint4*>(vg + off);
+    } else {
+      t.k[i] = make_uint4(0, 0, 0, 0);
+      t.v[i] = make_uint4(0, 0, 0, 0);
+    }
+  }
+}
+
+__device__ __forceinline__ void tile_store(const TileRegs& t, char* Ks, char* Vs, int tid) {
+  const int c = tid & 15;
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const int r = (tid >> 4) + 16 * i;
+    const int off = tile_off(r, c);
+    *reinterpret_cast<uint4*>(Ks + off) = t.k[i];
+    *reinterpret_cast<uint4*>(Vs + off) = t.v[i];
+  }
+}
+
+__global__ void __launch_bounds__(NTHREADS, 2) k_fwd_bf16(FwdParams p) {
+  extern __shared__ __align__(16) char smem[];
+  char* Ks = smem;
+  char* Vs = smem + TILE_BYTES;
+
+  // XCD-aware mapping: consecutive workgroup ids go round-robin over the 8 XCDs, so give every
+  // XCD a contiguous range of (head, query tile) items; its workgroups then share K/V in its L2.
+  const int bid = blockIdx.x;
+  const int item = (bid & 7) * p.per_xcd + (bid >> 3);
+  if (item >= p.total) return;
+  const int head = item / p.ntq;
+  int tq = item % p.ntq;
+  if (p.causal) tq = p.ntq - 1 - tq;      // longest rows first
+  const int kh = head / p.group;
+  const int q0 = tq * BM;
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int r32 = lane & 31, hh = lane >> 5;
+  const int q0w = q0 + wave * 32;
+  const int qrow = q0w + r32;
+  const bool qvalid = qrow < p.s_q;
+
+  const __bf16* kg = p.k + kh * p.kv_sh;
+  const __bf16* vg = p.v + kh * p.kv_sh;
+
+  // Q^T operand: lane holds Q[qrow][16 ks + 8 hh .. +7]
+  bf16x8 qreg[8];
+  {
+    const __bf16* qp = p.q + head * p.q_sh + static_cast<int64_t>(qrow) * p.q_ss + 8 * hh;
+#pragma unroll
+    for (int ks = 0; ks < 8; ++ks) {
+      uint4 raw = make_uint4(0, 0, 0, 0);
+      if (qvalid) raw = *reinterpret_cast<const uint4*>(qp + 16 * ks);
+      qreg[ks] = __builtin_bit_cast(bf16x8, raw);
+    }
+  }
+
+  f32x16 o[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int j = 0; j < 16; ++j) o[i][j] = 0.f;
+  float m_run = -INFINITY;     // running maximum of the raw scores q.k
+  float l_run = 0.f;           // this lane's half of the running row sum
+  const float c2 = p.scale * LOG2E;
+
+  const int k_end = p.causal ? min(p.s_k, q0 + BM) : p.s_k;
+  const int ntiles = (k_end + BN - 1) / BN;
+
+  TileRegs tr;
+  tile_load(tr, kg, vg, p.kv_ss, 0, p.s_k, tid);
+  tile_store(tr, Ks, Vs, tid);
+  __syncthreads();
+
+  for (int it = 0; it < ntiles; ++it) {
+    const int k0 = it * BN;
+    const bool more = it + 1 < ntiles;
+    if (more) tile_load(tr, kg, vg, p.kv_ss, k0 + BN, p.s_k, tid);
+
+    const bool active = !(p.causal && k0 > q0w + 31);
+    if (active) {
+      // S^T = K Q^T : two 32-key blocks
+      f32x16 s[2];
+#pragma unroll
+      for (int nb = 0; nb < 2; ++nb) {
+#pragma unroll
+        for (int j = 0; j < 16; ++j) s[nb][j] = 0.f;
+#pragma unroll
+        for (int ks = 0; ks < 8; ++ks) {
+          const bf16x8 a = lds_read_b128(Ks, tile_off(nb * 32 + r32, ks * 2 + hh));
+          s[nb] = mfma32(a, qreg[ks], s[nb]);
+        }
+      }
+      const bool need_mask = (k0 + BN > p.s_k) || (p.causal && k0 + BN - 1 > q0w);
+      if (need_mask) {
+#pragma unroll
+        for (int nb = 0; nb < 2; ++nb)
+#pragma unroll
+          for (int j = 0; j < 16; ++j) {
+            const int kv = k0 + nb * 32 + (j >> 2) * 8 + hh * 4 + (j & 3);
+            if (kv >= p.s_k || (p.causal && kv > qrow)) s[nb][j] = -INFINITY;
+          }
+      }
+      // online softmax in the exp2 domain (scores scaled by scale*log2 e)
+      float mx = s[0][0];
+#pragma unroll
+      for (int j = 1; j < 16; ++j) mx = fmaxf(mx, s[0][j]);
+#pragma unroll
+      for (int j = 0; j < 16; ++j) mx = fmaxf(mx, s[1][j]);
+      mx = fmaxf(mx, __shfl_xor(mx, 32));
+      const float m_new = fmaxf(m_run, mx);
+      const float mc = (m_new == -INFINITY) ? 0.f : m_new * c2;
+      const float alpha = __builtin_amdgcn_exp2f(m_run * c2 - mc);
+      float sum = 0.f;
+#pragma unroll
+      for (int nb = 0; nb < 2; ++nb)
+#pragma unroll
+        for (int j = 0; j < 16; ++j) {
+          const float e = __builtin_amdgcn_exp2f(fmaf(s[nb][j], c2, -mc));
+          s[nb][j] = e;
+          sum += e;
+        }
+      l_run = l_run * alpha + sum;
+      m_run = m_new;
+      if (!__all(alpha == 1.f)) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+#pragma unroll
+          for (int j = 0; j < 16; ++j) o[i][j] *= alpha;
+      }
+      // O^T += V^T P^T : 4 contraction steps of 16 keys, 4 blocks of 32 output columns
+#pragma unroll
+      for (int kk = 0; kk < 4; ++kk) {
+        const bf16x8 pb = pack8(s[kk >> 1], (kk & 1) * 8);
+#pragma unroll
+        for (int db = 0; db < 4; ++db) {
+          const bf16x8 a = lds_gather_rows(Vs, kk * 16, db * 32, lane);
+          o[db] = mfma32(a, pb, o[db]);
+        }
+      }
+    }
+    __syncthreads();
+    if (more) tile_store(tr, Ks, Vs, tid);
+    __syncthreads();
+  }
+
+  // epilogue: combine the two half-sums, normalise, write O and the logsumexp
+  const float l_tot = l_run + __shfl_xor(l_run, 32);
+  const float inv = l_tot > 0.f ? 1.f / l_tot : 0.f;
+  if (qvalid) {
+    if (hh == 0) p.lse[head * p.l_sh + qrow] = l_tot > 0.f ? m_run * p.scale + logf(l_tot) : -INFINITY;
+    const int64_t obase = head * p.o_sh + static_cast<int64_t>(qrow) * p.o_ss;
+#pragma unroll
+    for (int db = 0; db < 4; ++db)
+#pragma unroll
+      for (int g4 = 0; g4 < 4; ++g4) {
+        const int col = db * 32 + g4 * 8 + hh * 4;
+        const float x0 = o[db][g4 * 4 + 0] * inv, x1 = o[db][g4 * 4 + 1] * inv;
+        const float x2 = o[db][g4 * 4 + 2] * inv, x3 = o[db][g4 * 4 + 3] * inv;
+        if (p.o_bf16) {
+          bf16x4 b; b[0] = static_cast<__bf16>(x0); b[1] = static_cast<__bf16>(x1);
+          b[2] = static_cast<__bf16>(x2); b[3] = static_cast<__bf16>(x3);
+          *reinterpret_cast<bf16x4*>(static_cast<__bf16*>(p.o) + obase + col) = b;
+        } else {
+          *reinterpret_cast<float4*>(static_cast<float*>(p.o) + obase + col) = make_float4(x0, x1, x2, x3);
+        }
+      }
+  }
+}
+
+}  // namespace
+
+int launch_fwd_bf16(const dfa_shape& sh, const void* q, const void* k, const void* v,
+                    void* o, float* lse, hipStream_t st) {
+  FwdParams p{};
+  p.q = static_cast<const __bf16*>(q); p.k = static_cast<const __bf16*>(k); p.v = static_cast<const __bf16*>(v);
+  p.o = o; p.lse = lse;
+  p.s_q = sh.s_q; p.s_k = sh.s_k; p.h_q = sh.h_q; p.group = sh.h_q / sh.h_kv; p.causal = sh.causal;
+  p.o_bf16 = sh.o_dtype == DFA_BF16; p.scale = sh.scale;
+  p.q_sh = sh.q_stride_h; p.q_ss = sh.q_stride_s; p.kv_sh = sh.kv_stride_h; p.kv_ss = sh.kv_stride_s;
+  p.o_sh = sh.o_stride_h; p.o_ss = sh.o_stride_s; p.l_sh = sh.lse_stride_h;
+  p.ntq = (sh.s_q + BM - 1) / BM;
+  const int64_t total = static_cast<int64_t>(p.ntq) * sh.h_q;
+  if (total > (1 << 30)) return DFA_ERR_SHAPE;
+  p.total = static_cast<int>(total);
+  p.per_xcd = (p.total + 7) / 8;
+  k_fwd_bf16<<<p.per_xcd * 8, NTHREADS, 2 * TILE_BYTES, st>>>(p);
+  return last_launch_status();
+}
+
+}  // namespace dfa

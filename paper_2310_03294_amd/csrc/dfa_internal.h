@@ -9,8 +9,8 @@
 namespace dfa {
 
 // Launch wrappers: every one validates nothing (the ABI layer did) and returns a dfa_status.
-int launch_merge(int64_t rows, int d, int o_dtype, void* o_a, int64_t sa, float* lse_a,
-                 const void* o_b, int64_t sb, const float* lse_b, hipStream_t st);
+int launch_merge(const dfa_merge_desc& md, void* o_a, float* lse_a, const void* o_b, const float* lse_b,
+                 hipStream_t st);
 int launch_delta(const dfa_shape& sh, const void* o, const void* dO, float* delta, hipStream_t st);
 int launch_fill_zero_rows(float* p, int heads, int rows, int d, int64_t stride_h, int64_t stride_s,
                           hipStream_t st);

@@ -98,12 +98,23 @@ def test_null_and_alignment_errors(lib):
     assert lib.dfa_chunk_bwd(ctypes.byref(_shape(dq_stride_s=8)), FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE,
                              FAKE, 0, None) == -2
     assert lib.dfa_delta(ctypes.byref(sh), FAKE, None, FAKE, None) == -1
-    assert lib.dfa_merge(-1, 64, B.DFA_F32, FAKE, 64, FAKE, FAKE * 2, 64, FAKE * 2, None) == -2
-    assert lib.dfa_merge(8, 48, B.DFA_F32, FAKE, 64, FAKE, FAKE * 2, 64, FAKE * 2, None) == -2
-    assert lib.dfa_merge(8, 64, 7, FAKE, 64, FAKE, FAKE * 2, 64, FAKE * 2, None) == -3
-    assert lib.dfa_merge(8, 64, B.DFA_F32, FAKE, 64, FAKE, FAKE, 64, FAKE * 2, None) == -4   # aliasing
-    assert lib.dfa_merge(8, 64, B.DFA_F32, None, 64, FAKE, FAKE * 2, 64, FAKE * 2, None) == -1
-    assert lib.dfa_merge(0, 64, B.DFA_F32, FAKE, 64, FAKE, FAKE * 2, 64, FAKE * 2, None) == 0   # empty: no-op
+    def md(**kw):
+        m = B.DfaMergeDesc()
+        base = dict(heads=2, rows=8, d=64, o_dtype=B.DFA_F32, a_stride_h=512, a_stride_s=64, lse_a_stride_h=8,
+                    b_stride_h=512, b_stride_s=64, lse_b_stride_h=8)
+        base.update(kw)
+        for k, v in base.items():
+            setattr(m, k, v)
+        return ctypes.byref(m)
+    assert lib.dfa_merge(md(rows=-1), FAKE, FAKE, FAKE * 2, FAKE * 2, None) == -2
+    assert lib.dfa_merge(md(d=48), FAKE, FAKE, FAKE * 2, FAKE * 2, None) == -2
+    assert lib.dfa_merge(md(o_dtype=7), FAKE, FAKE, FAKE * 2, FAKE * 2, None) == -3
+    assert lib.dfa_merge(md(a_stride_s=60), FAKE, FAKE, FAKE * 2, FAKE * 2, None) == -2
+    assert lib.dfa_merge(md(lse_b_stride_h=4), FAKE, FAKE, FAKE * 2, FAKE * 2, None) == -2
+    assert lib.dfa_merge(md(), FAKE, FAKE, FAKE, FAKE * 2, None) == -4   # aliasing
+    assert lib.dfa_merge(md(), None, FAKE, FAKE * 2, FAKE * 2, None) == -1
+    assert lib.dfa_merge(None, FAKE, FAKE, FAKE * 2, FAKE * 2, None) == -1
+    assert lib.dfa_merge(md(rows=0, lse_a_stride_h=0, lse_b_stride_h=0), FAKE, FAKE, FAKE * 2, FAKE * 2, None) == 0
 
 
 def test_empty_query_chunk_is_noop(lib):
