@@ -1,0 +1,179 @@
+#!/usr/bin/env python3
+"""Benchmark of the DistFlashAttn per-worker hot path on one MI355X.
+
+One "step" = one pass of the whole hot path for the heaviest worker (worker P-1) of the
+Llama-7B attention shape at N = 32768, P = 8 (chunk 4096, 32 heads x d128, bf16): the causal
+diagonal chunk, its four OWN off-diagonal pairs with their merges, the merges of the three
+partials that helpers send, the D pre-pass and the backward of the same five pairs.
+Inputs are resident in HBM before the timed region; the helpers' partials are produced
+beforehand (they arrive over the network in the distributed setting).
+
+Prints ONE JSON line: causal-adjusted TFLOP/s (14 d H nnz / t), the MFMA roofline of the
+dominant kernel measured with HIP events inside the timed region, and the fp64 CPU oracle
+timed on a bounded sample of the same workload.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0      # MI355X dense bf16 MFMA, published
+PEAK_HBM_GBS = 8000.0
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--config", type=int, default=1, help="index into dfa_inputs.CONFIGS (1 = the metric's workload)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-heads", type=int, default=2, help="heads of the share the oracle is timed on")
+    return ap.parse_args()
+
+
+def share_pairs(sched):
+    return [(s.q_chunk, s.kv_chunk, s.kind) for s in sched if s.kind != 0]
+
+
+def traffic_from_profiles(name):
+    """HBM bytes per launch of the dominant kernel, measured offline with rocprofv3 --pmc
+    (FETCH_SIZE + WRITE_SIZE) and recorded in profiles/; None when not recorded."""
+    path = os.path.join(ROOT, "profiles", name)
+    try:
+        for line in open(path):
+            if line.startswith("traffic_bytes_per_launch"):
+                return float(line.split("=")[1].split()[0])
+    except OSError:
+        pass
+    return None
+
+
+def cpu_baseline(w, worker, heads, q, k, v, do):
+    """Times the fp64 oracle (as it stands) on `heads` heads of the worker's share: pair
+    forward + pair backward of its five pairs.  Returns the cpu_baseline JSON object."""
+    import numpy as np
+    from oracle import attention as A
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([i.get("num_threads", 1) for i in threadpool_info()] or [1])
+    except Exception:
+        cores = os.cpu_count()
+    c = w.chunk
+    kvh = max(1, heads // (w.h_q // w.h_kv))
+    q64 = q[:heads].double().numpy(); do64 = do[:heads].double().numpy()
+    k64 = k[:kvh].double().numpy(); v64 = v[:kvh].double().numpy()
+    # global logsumexp and D of the worker's rows (untimed set-up: the backward's saved inputs)
+    rows = slice(worker * c, (worker + 1) * c)
+    O = np.empty((heads, c, w.d)); L = np.empty((heads, c))
+    for h in range(heads):
+        O[h], L[h] = A.rows_fwd(q64[h, rows], np.arange(worker * c, (worker + 1) * c), k64[h // (heads // kvh)],
+                                v64[h // (heads // kvh)], w.scale)
+    Lfull = np.zeros((heads, w.n_total)); Dfull = np.zeros((heads, w.n_total))
+    Lfull[:, rows] = L; Dfull[:, rows] = A.delta_rows(O, do64[:, rows])
+    import paper_2310_03294_amd as dfa
+    pairs = share_pairs(dfa.dfa_schedule(w.p, worker))
+    t0 = time.perf_counter()
+    for (qc, kc, _kind) in pairs:
+        A.pair_fwd(q64, k64, v64, w.scale, qc, kc, c)
+        A.pair_bwd(q64, k64, v64, do64, Lfull, Dfull, w.scale, qc, kc, c)
+    dt = time.perf_counter() - t0
+    nnz = sum(c * (c + 1) // 2 if qc == kc else c * c for qc, kc, _ in pairs)
+    flops = 14.0 * w.d * heads * nnz
+    return {"value": flops / dt / 1e12, "unit": "TFLOP/s", "cores": int(cores), "kind": "oracle",
+            "sample": f"{heads} of {w.h_q} heads of worker {worker}'s share ({len(pairs)} pairs fwd+bwd, fp64 numpy), "
+                      f"{dt:.1f} s"}
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU (the P workers are virtual); --gpus must be 1", file=sys.stderr)
+        sys.exit(2)
+    import torch
+    import dfa_inputs
+    import paper_2310_03294_amd as dfa
+    from paper_2310_03294_amd import driver, binding as B
+
+    dfa.load_library()           # fails loudly if the HIP extension is missing
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    dev = torch.device("cuda:0")
+    w = dfa_inputs.CONFIGS[args.config]
+    worker = w.p - 1
+    c = w.chunk
+
+    q, k, v, do = (dfa_inputs.full_sequence(w, t) for t in range(4))
+    Q, K, V, dO = (t.to(dev) for t in (q, k, v, do))
+    bufs = driver.Buffers(w.h_q, w.h_kv, w.n_total, w.d, w.p, dev)
+    remote = driver.helper_partials_for(Q, K, V, w.scale, w.p, worker, bufs)
+    sched = dfa.dfa_schedule(w.p, worker)
+    pairs = share_pairs(sched)
+    nnz = sum(c * (c + 1) // 2 if qc == kc else c * c for qc, kc, _ in pairs)
+    flops_step = 14.0 * w.d * w.h_q * nnz
+
+    def chunk(t, i):
+        return t[:, i * c:(i + 1) * c]
+
+    ev_bwd = []     # (start, end, flops) per backward-kernel launch inside the timed region
+
+    def step(record):
+        driver.forward_worker(Q, K, V, w.scale, w.p, worker, bufs, remote=remote)
+        B.dfa_delta(chunk(bufs.O, worker), chunk(dO, worker), delta=chunk(bufs.delta, worker))
+        for (qc, kc, kind) in pairs:
+            if record:
+                e0 = torch.cuda.Event(enable_timing=True); e1 = torch.cuda.Event(enable_timing=True)
+                e0.record()
+            B.dfa_chunk_bwd(chunk(Q, qc), chunk(K, kc), chunk(V, kc), chunk(bufs.L, qc), chunk(bufs.delta, qc),
+                            chunk(dO, qc), chunk(bufs.dQ, qc), chunk(bufs.dK, kc), chunk(bufs.dV, kc),
+                            kind == B.DFA_STEP_DIAG, w.scale, accumulate=True)
+            if record:
+                e1.record()
+                n = c * (c + 1) // 2 if qc == kc else c * c
+                ev_bwd.append((e0, e1, 10.0 * w.d * w.h_q * n))
+
+    for _ in range(args.warmup):
+        step(False)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step(True)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    ms = dt * 1e3 / args.steps
+    tflops = flops_step / (ms * 1e-3) / 1e12
+
+    bwd_ms = sum(a.elapsed_time(b) for a, b, _ in ev_bwd)
+    bwd_fl = sum(f for _, _, f in ev_bwd)
+    achieved = bwd_fl / (bwd_ms * 1e-3) / 1e12
+    roofline = {"bound": "mfma", "kernel": "k_bwd_bf16", "achieved": round(achieved, 2), "peak": PEAK_BF16_TFLOPS,
+                "unit": "TFLOP/s", "frac": round(achieved / PEAK_BF16_TFLOPS, 4),
+                "avg_launch_ms": round(bwd_ms / len(ev_bwd), 4),
+                "flop_per_launch": bwd_fl / len(ev_bwd),
+                "traffic": traffic_from_profiles("k_bwd_bf16_cfg2_pmc.txt")}
+
+    out = {
+        "metric": "causal-adjusted attention TFLOP/s fwd+bwd per worker share; % of bf16 MFMA peak",
+        "value": round(tflops, 2), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16" if w.dtype == "bf16" else "f32", "data": "synthetic",
+        "config": {"workload": f"{w.name}: worker {worker} share, {len(pairs)} pairs fwd+bwd + "
+                               f"{len(remote)} remote merges, H={w.h_q}/{w.h_kv} d={w.d} C={c}",
+                   "n_total": w.n_total, "P": w.p, "chunk": c},
+        "pct_of_bf16_peak": round(100.0 * tflops / PEAK_BF16_TFLOPS, 2),
+        "flop_per_step": flops_step,
+        "roofline": roofline,
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(w, worker, args.cpu_heads, q, k, v, do)
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()

@@ -20,7 +20,7 @@ constexpr int D = 128;
 constexpr int BM = 128;     // query rows per workgroup
 constexpr int BN = 64;      // key rows per LDS tile
 constexpr int NTHREADS = 256;
-constexpr int TILE_BYTES = BN * D * 2;
+constexpr int TILE_BYTES = BN * kRowBytes;   // rows padded to 272 B
 constexpr float LOG2E = 1.4426950408889634f;
 
 struct FwdParams {
@@ -82,6 +82,8 @@ __global__ void __launch_bounds__(NTHREADS, 2) k_fwd_bf16(FwdParams p) {
   const int q0w = q0 + wave * 32;
   const int qrow = q0w + r32;
   const bool qvalid = qrow < p.s_q;
+  const int a_base = tile_off(r32, hh);     // per-lane LDS bases; the rest of every address is constant
+  const int g_base = gather_base(lane);
 
   const __bf16* kg = p.k + kh * p.kv_sh;
   const __bf16* vg = p.v + kh * p.kv_sh;
@@ -130,7 +132,7 @@ __global__ void __launch_bounds__(NTHREADS, 2) k_fwd_bf16(FwdParams p) {
         for (int j = 0; j < 16; ++j) s[nb][j] = 0.f;
 #pragma unroll
         for (int ks = 0; ks < 8; ++ks) {
-          const bf16x8 a = lds_read_b128(Ks, tile_off(nb * 32 + r32, ks * 2 + hh));
+          const bf16x8 a = lds_read_b128(Ks, a_base + nb * 32 * kRowBytes + ks * 32);
           s[nb] = mfma32(a, qreg[ks], s[nb]);
         }
       }
@@ -177,7 +179,7 @@ __global__ void __launch_bounds__(NTHREADS, 2) k_fwd_bf16(FwdParams p) {
         const bf16x8 pb = pack8(s[kk >> 1], (kk & 1) * 8);
 #pragma unroll
         for (int db = 0; db < 4; ++db) {
-          const bf16x8 a = lds_gather_rows(Vs, kk * 16, db * 32, lane);
+          const bf16x8 a = lds_gather(Vs, g_base + kk * 16 * kRowBytes + db * 64);
           o[db] = mfma32(a, pb, o[db]);
         }
       }

@@ -10,10 +10,12 @@
 // C[.][r] with i in [8u, 8u+8) become B[8h+e][r], provided the A operand of that product is
 // gathered with the same row order, rows (e/4)*8 + 4h + e%4 of the 16-row block u.
 //
-// LDS tiles hold rows of 128 bf16 (256 B, sixteen 16-byte chunks) without padding; chunk c
-// of row r is stored at chunk position c ^ swz(r).  With swz(r) = ((r&3)<<2) | ((r>>2)&3)
-// both access patterns used here are bank-conflict free: ds_read_b128 of one chunk column
-// from 16 consecutive rows, and ds_read_b64_tr_b16 of 4 rows x 64 B.
+// LDS tiles hold rows of 128 bf16 padded to 272 bytes, and logical row r is stored at physical
+// row prow(r) (a 4x4 transpose of the low four row bits).  With that, both access patterns
+// used here are bank-conflict free AND every address is a per-lane base plus a compile-time
+// constant: ds_read_b128 of one 16-byte chunk column from 16 consecutive logical rows (their
+// physical rows are 16 distinct values mod 16, and 272 = 256 + 16), and ds_read_b64_tr_b16 of
+// 4 consecutive logical rows x 64 B (their physical rows are 4 apart: 4 * 272 = 64 mod 256).
 #pragma once
 
 #include <hip/hip_runtime.h>
@@ -33,10 +35,56 @@ __device__ __forceinline__ f32x16 mfma32(bf16x8 a, bf16x8 b, f32x16 c) {
   return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
 }
 
-__device__ __forceinline__ int swz(int r) { return ((r & 3) << 2) | ((r >> 2) & 3); }
+// The same instruction with the register file of each operand fixed by hand.  gfx950 has 256
+// architectural VGPRs (the only ones VALU instructions can touch) and 256 accumulation VGPRs
+// (AGPRs) per lane at one wavefront per SIMD.  A kernel whose MFMA-only state (long-lived
+// accumulators, loop-invariant B operands) is pinned in AGPRs keeps the VGPRs free for the
+// softmax arithmetic and for LDS reads in flight.  Suffixes: accumulator file (a|v), then the
+// files of the A and B operands.  "z" forms start a chain with C = 0.  "_last" forms end a
+// chain whose result is read by VALU instructions next: the hardware does not interlock that
+// read, so they carry the wait states themselves (16 cover the 8-pass 32x32x16 MFMA).
+__device__ __forceinline__ void mfma_a_vv(f32x16& acc, bf16x8 a, bf16x8 b) {
+  asm("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+a"(acc) : "v"(a), "v"(b));
+}
+__device__ __forceinline__ void mfma_vz_va(f32x16& acc, bf16x8 a, bf16x8 b) {
+  asm("v_mfma_f32_32x32x16_bf16 %0, %1, %2, 0" : "=&v"(acc) : "v"(a), "a"(b));
+}
+__device__ __forceinline__ void mfma_v_va(f32x16& acc, bf16x8 a, bf16x8 b) {
+  asm("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(acc) : "v"(a), "a"(b));
+}
+__device__ __forceinline__ void mfma_v_va_last(f32x16& acc, bf16x8 a, bf16x8 b) {
+  asm("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0\n\ts_nop 15" : "+v"(acc) : "v"(a), "a"(b));
+}
+__device__ __forceinline__ void mfma_vz_vv(f32x16& acc, bf16x8 a, bf16x8 b) {
+  asm("v_mfma_f32_32x32x16_bf16 %0, %1, %2, 0" : "=&v"(acc) : "v"(a), "v"(b));
+}
+__device__ __forceinline__ void mfma_v_vv(f32x16& acc, bf16x8 a, bf16x8 b) {
+  asm("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(acc) : "v"(a), "v"(b));
+}
+__device__ __forceinline__ void mfma_v_vv_last(f32x16& acc, bf16x8 a, bf16x8 b) {
+  asm("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0\n\ts_nop 15" : "+v"(acc) : "v"(a), "v"(b));
+}
 
-// byte offset of 16-byte chunk c of row r inside a 256-B-per-row tile
-__device__ __forceinline__ int tile_off(int r, int c) { return r * 256 + ((c ^ swz(r)) << 4); }
+// Moves a loop-invariant MFMA operand into AGPRs for good.
+__device__ __forceinline__ bf16x8 to_agpr(bf16x8 x) {
+  typedef int i32x4 __attribute__((ext_vector_type(4)));
+  const i32x4 v = __builtin_bit_cast(i32x4, x);
+  i32x4 r;
+  asm volatile("v_accvgpr_write_b32 %0, %1" : "=a"(r[0]) : "v"(v[0]));
+  asm volatile("v_accvgpr_write_b32 %0, %1" : "=a"(r[1]) : "v"(v[1]));
+  asm volatile("v_accvgpr_write_b32 %0, %1" : "=a"(r[2]) : "v"(v[2]));
+  asm volatile("v_accvgpr_write_b32 %0, %1" : "=a"(r[3]) : "v"(v[3]));
+  return __builtin_bit_cast(bf16x8, r);
+}
+
+#define DFA_SCHED_FENCE() __builtin_amdgcn_sched_barrier(0)
+
+constexpr int kRowBytes = 272;
+
+__device__ __forceinline__ int prow(int r) { return (r & ~15) | ((r & 3) << 2) | ((r >> 2) & 3); }
+
+// byte offset of 16-byte chunk c of logical row r
+__device__ __forceinline__ int tile_off(int r, int c) { return prow(r) * kRowBytes + (c << 4); }
 
 __device__ __forceinline__ bf16x8 lds_read_b128(const char* base, int off) {
   return *reinterpret_cast<const bf16x8*>(base + off);
@@ -51,16 +99,19 @@ __device__ __forceinline__ bf16x4 lds_read_tr(const char* base, int off) {
   return __builtin_bit_cast(bf16x4, v);
 }
 
-// 8 values for the A operand of a product whose contraction runs over tile ROWS (the tile is
-// stored row-major, so this is a transposed gather): rows row0 + (e/4)*8 + 4h + e%4, column
-// col0 + (lane % 32).  row0 must be a multiple of 16, col0 a multiple of 32.
-__device__ __forceinline__ bf16x8 lds_gather_rows(const char* base, int row0, int col0, int lane) {
+// Gather for an operand whose contraction runs over tile ROWS (the tile is stored row-major, so
+// this is a transposed read).  gather_base(lane) is the per-lane part; lds_gather(base, off)
+// with off = row0 * kRowBytes + col0 * 2 (row0 a multiple of 16, col0 a multiple of 32) returns
+// the 8 values  tile[row0 + (e/4)*8 + 4h + e%4][col0 + lane%32],  e = 0..7,  h = lane/32,
+// which is the row order in which an MFMA result tile is fed back as a B operand.
+__device__ __forceinline__ int gather_base(int lane) {
   const int g = lane >> 4, j = lane & 15;
-  const int row = row0 + 4 * (g >> 1) + (j >> 2);
-  const int c = (col0 >> 3) + 2 * (g & 1) + ((j & 3) >> 1);
-  const int sub = (j & 1) << 3;
-  const bf16x4 lo = lds_read_tr(base, tile_off(row, c) + sub);
-  const bf16x4 hi = lds_read_tr(base, tile_off(row + 8, c) + sub);
+  return tile_off(4 * (g >> 1) + (j >> 2), 2 * (g & 1) + ((j & 3) >> 1)) + ((j & 1) << 3);
+}
+
+__device__ __forceinline__ bf16x8 lds_gather(const char* base, int off) {
+  const bf16x4 lo = lds_read_tr(base, off);
+  const bf16x4 hi = lds_read_tr(base, off + 2 * kRowBytes);   // logical rows +8 = physical rows +2
   return __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
 }
 
