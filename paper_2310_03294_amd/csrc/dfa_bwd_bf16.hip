@@ -13,10 +13,6 @@
 //                                       each wavefront reduces over all 128 keys of the workgroup
 //                                       for its 32 output columns, then fp32 atomics to dq)
 // dk, dv are written once per workgroup (summed over the group's query heads in registers).
-//
-// The tile body exists twice: an interior version without any bounds or mask logic (one
-// straight-line block the scheduler can software-pipeline: the MFMAs of one 32-query block
-// run under the exp/VALU work of the other) and an edge version for ragged or diagonal tiles.
 #include "dfa_internal.h"
 #include "dfa_mfma.h"
 
@@ -27,7 +23,7 @@ constexpr int D = 128;
 constexpr int BN = 128;    // key rows per workgroup
 constexpr int BM = 64;     // query rows per LDS tile
 constexpr int NTHREADS = 256;
-constexpr int QTILE_BYTES = BM * kRowBytes;    // 17 KB (rows padded to 272 B)
+constexpr int QTILE_BYTES = BM * kRowBytes;       // rows padded to 272 B
 constexpr int DST_BYTES = (BN / 2) * kRowBytes;   // dS^T as 64 padded rows, two keys per row
 constexpr float LOG2E = 1.4426950408889634f;
 
@@ -42,7 +38,6 @@ struct BwdParams {
 
 struct QTileRegs { uint4 q[4], g[4]; float ld; };
 
-template <bool EDGE>
 __device__ __forceinline__ void qtile_load(QTileRegs& t, const BwdParams& p, int hq, int q0, int tid) {
   const int c = tid & 15;
   const __bf16* qg = p.q + hq * p.q_sh;
@@ -50,7 +45,7 @@ __device__ __forceinline__ void qtile_load(QTileRegs& t, const BwdParams& p, int
 #pragma unroll
   for (int i = 0; i < 4; ++i) {
     const int r = (tid >> 4) + 16 * i;
-    if (!EDGE || q0 + r < p.s_q) {
+    if (q0 + r < p.s_q) {
       const int64_t off = static_cast<int64_t>(q0 + r) * p.q_ss + c * 8;
       t.q[i] = *reinterpret_cast<const uint4*>(qg + off);
       t.g[i] = *reinterpret_cast<const uint4*>(gg + off);
@@ -63,14 +58,12 @@ __device__ __forceinline__ void qtile_load(QTileRegs& t, const BwdParams& p, int
   t.ld = 0.f;
   if (tid < 128) {
     const int r = tid & 63;
-    const bool ok = !EDGE || q0 + r < p.s_q;
-    const int idx = ok ? q0 + r : 0;
+    const bool ok = q0 + r < p.s_q;
     if (tid < 64) {
-      const float L = p.lse[hq * p.l_sh + idx];
-      t.ld = (ok && L > -INFINITY) ? L * LOG2E : INFINITY;   // +inf makes P exactly 0 for that row
+      const float L = ok ? p.lse[hq * p.l_sh + q0 + r] : INFINITY;
+      t.ld = (L > -INFINITY) ? L * LOG2E : INFINITY;   // +inf makes P exactly 0 for that row
     } else {
-      const float dl = p.delta[hq * p.l_sh + idx];
-      t.ld = ok ? dl : 0.f;
+      t.ld = ok ? p.delta[hq * p.l_sh + q0 + r] : 0.f;
     }
   }
 }
@@ -103,13 +96,12 @@ __global__ void __launch_bounds__(NTHREADS, 1) k_bwd_bf16(BwdParams p) {
   char* Ts = smem + 2 * QTILE_BYTES;       // 16 KB  (dS^T tile)
   float* LDs = reinterpret_cast<float*>(smem + 2 * QTILE_BYTES + DST_BYTES);   // lse'[64], D[64]
 
-  // XCD-aware mapping: workgroup ids go round-robin over the 8 XCDs; give every XCD a contiguous
-  // range of (kv head, key tile) items so that the tiles of one head share Q/dO in one L2.
   const int bid = blockIdx.x;
   const int item = (bid & 7) * p.per_xcd + (bid >> 3);
   if (item >= p.total) return;
   const int kh = item / p.ntk;
-  const int tk = item % p.ntk;       // causal: low key tiles meet the most query tiles and come first
+  int tk = item % p.ntk;
+  // causal: key tile 0 meets every query tile, so low tiles are the long ones and go first
   const int k0 = tk * BN;
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -126,12 +118,14 @@ __global__ void __launch_bounds__(NTHREADS, 1) k_bwd_bf16(BwdParams p) {
   // K^T and V^T B operands of this wavefront's 32 keys (contraction over d)
   bf16x8 kT[8], vT[8];
   {
-    const int64_t off = kh * p.kv_sh + static_cast<int64_t>(kvalid ? kvrow : 0) * p.kv_ss + 8 * hh;
+    const int64_t off = kh * p.kv_sh + static_cast<int64_t>(kvrow) * p.kv_ss + 8 * hh;
 #pragma unroll
     for (int ks = 0; ks < 8; ++ks) {
-      uint4 a = *reinterpret_cast<const uint4*>(p.k + off + 16 * ks);
-      uint4 b = *reinterpret_cast<const uint4*>(p.v + off + 16 * ks);
-      if (!kvalid) { a = make_uint4(0, 0, 0, 0); b = make_uint4(0, 0, 0, 0); }
+      uint4 a = make_uint4(0, 0, 0, 0), b = make_uint4(0, 0, 0, 0);
+      if (kvalid) {
+        a = *reinterpret_cast<const uint4*>(p.k + off + 16 * ks);
+        b = *reinterpret_cast<const uint4*>(p.v + off + 16 * ks);
+      }
       kT[ks] = __builtin_bit_cast(bf16x8, a);
       vT[ks] = __builtin_bit_cast(bf16x8, b);
     }
@@ -165,150 +159,98 @@ __global__ void __launch_bounds__(NTHREADS, 1) k_bwd_bf16(BwdParams p) {
   const int q_begin = p.causal ? k0 : 0;            // k0 is a multiple of BM
   const int ntq = (p.s_q - q_begin + BM - 1) / BM;  // query tiles per head for this key tile
   const int niter = ntq * p.group;
-  const bool k_edge = k0 + BN > p.s_k;
 
   QTileRegs tr;
   if (niter > 0) {
-    qtile_load<true>(tr, p, kh * p.group, q_begin, tid);
+    qtile_load(tr, p, kh * p.group, q_begin, tid);
     qtile_store(tr, Qs, Gs, LDs, tid);
   }
   __syncthreads();
-
-  // ---- tile body -------------------------------------------------------------------------
-  auto phase_a = [&](int qb, f32x16& s, f32x16& dp) {     // S = Q K^T, dP = dO V^T (32 queries)
-#pragma unroll
-    for (int j = 0; j < 16; ++j) { s[j] = 0.f; dp[j] = 0.f; }
-#pragma unroll
-    for (int ks = 0; ks < 8; ++ks) {
-      const int off = a_base + qb * 32 * kRowBytes + ks * 32;
-      s = mfma32(lds_read_b128(Qs, off), kT[ks], s);
-      dp = mfma32(lds_read_b128(Gs, off), vT[ks], dp);
-    }
-  };
-  auto phase_c = [&](int qb, const f32x16& pr, const f32x16& ds) {   // dV^T += dO^T P, dK^T += Q^T dS
-#pragma unroll
-    for (int u = 0; u < 2; ++u) {
-      const bf16x8 pb = pack8(pr, u * 8);
-      const bf16x8 sb = pack8(ds, u * 8);
-      const int roff = g_base + (qb * 32 + u * 16) * kRowBytes;
-#pragma unroll
-      for (int db = 0; db < 4; ++db) {
-        dvT[db] = mfma32(lds_gather(Gs, roff + db * 64), pb, dvT[db]);
-        dkT[db] = mfma32(lds_gather(Qs, roff + db * 64), sb, dkT[db]);
-      }
-    }
-  };
-  auto write_ds = [&](int qb, const f32x16& ds) {
-#pragma unroll
-    for (int g4 = 0; g4 < 4; ++g4) {
-      bf16x4 b;
-#pragma unroll
-      for (int e = 0; e < 4; ++e) b[e] = static_cast<__bf16>(ds[g4 * 4 + e]);
-      *reinterpret_cast<bf16x4*>(Ts + w_base + (qb * 32 + g4 * 8) * 2) = b;
-    }
-  };
-  auto dq_block = [&](int qb, f32x16& dq) {                // dQ (32 queries x 32 columns) over 128 keys
-#pragma unroll
-    for (int j = 0; j < 16; ++j) dq[j] = 0.f;
-#pragma unroll
-    for (int ks = 0; ks < 8; ++ks) {
-      // keys +16 per step = logical rows +8: physical +16 rows on even steps, +2 more on odd ones;
-      // the second half of the operand (keys +8 = logical rows +4) sits one physical row further
-      const int off = t_base + ((ks >> 1) * 16 + (ks & 1) * 2) * kRowBytes + qb * 64;
-      dq = mfma32(cat8(lds_read_tr(Ts, off), lds_read_tr(Ts, off + kRowBytes)), kB[ks], dq);
-    }
-  };
 
   for (int it = 0; it < niter; ++it) {
     const int hq = kh * p.group + it / ntq;
     const int q0 = q_begin + (it % ntq) * BM;
     const bool more = it + 1 < niter;
-    if (more) {
-      const int hq_n = kh * p.group + (it + 1) / ntq;
-      const int q0_n = q_begin + ((it + 1) % ntq) * BM;
-      if (q0_n + BM <= p.s_q) qtile_load<false>(tr, p, hq_n, q0_n, tid);
-      else qtile_load<true>(tr, p, hq_n, q0_n, tid);
-    }
-    const bool edge = k_edge || (q0 + BM > p.s_q) || (p.causal && q0 < k0 + BN - 1);
+    if (more) qtile_load(tr, p, kh * p.group + (it + 1) / ntq, q_begin + ((it + 1) % ntq) * BM, tid);
 
-    f32x16 s0, dp0, s1, dp1;
-    if (!edge) {
-      // interior tile: straight-line code, MFMAs of one query block under the VALU work of the other
-      phase_a(0, s0, dp0);
-      phase_a(1, s1, dp1);
+    // S = Q K^T and dP = dO V^T for two 32-query blocks
+    f32x16 s[2], dp[2];
 #pragma unroll
-      for (int g4 = 0; g4 < 4; ++g4) {
-        const f32x4 L4 = *reinterpret_cast<const f32x4*>(LDs + g4 * 8 + hh * 4);
-        const f32x4 D4 = *reinterpret_cast<const f32x4*>(LDs + 64 + g4 * 8 + hh * 4);
+    for (int qb = 0; qb < 2; ++qb) {
 #pragma unroll
-        for (int e = 0; e < 4; ++e) {
-          const int j = g4 * 4 + e;
-          const float pr = __builtin_amdgcn_exp2f(fmaf(s0[j], c2, -L4[e]));
-          s0[j] = pr;
-          dp0[j] = pr * (dp0[j] - D4[e]);
-        }
-      }
-      phase_c(0, s0, dp0);
+      for (int j = 0; j < 16; ++j) { s[qb][j] = 0.f; dp[qb][j] = 0.f; }
 #pragma unroll
-      for (int g4 = 0; g4 < 4; ++g4) {
-        const f32x4 L4 = *reinterpret_cast<const f32x4*>(LDs + 32 + g4 * 8 + hh * 4);
-        const f32x4 D4 = *reinterpret_cast<const f32x4*>(LDs + 96 + g4 * 8 + hh * 4);
-#pragma unroll
-        for (int e = 0; e < 4; ++e) {
-          const int j = g4 * 4 + e;
-          const float pr = __builtin_amdgcn_exp2f(fmaf(s1[j], c2, -L4[e]));
-          s1[j] = pr;
-          dp1[j] = pr * (dp1[j] - D4[e]);
-        }
-      }
-      write_ds(0, dp0);
-      phase_c(1, s1, dp1);
-      write_ds(1, dp1);
-    } else {
-      // edge tile (ragged sizes or the causal diagonal): one query block at a time, masked
-#pragma unroll
-      for (int qb = 0; qb < 2; ++qb) {
-        phase_a(qb, s0, dp0);
-#pragma unroll
-        for (int g4 = 0; g4 < 4; ++g4) {
-          const int qi = qb * 32 + g4 * 8 + hh * 4;
-          const f32x4 L4 = *reinterpret_cast<const f32x4*>(LDs + qi);
-          const f32x4 D4 = *reinterpret_cast<const f32x4*>(LDs + 64 + qi);
-#pragma unroll
-          for (int e = 0; e < 4; ++e) {
-            const int j = g4 * 4 + e;
-            float pr = __builtin_amdgcn_exp2f(fmaf(s0[j], c2, -L4[e]));
-            const int qrow = q0 + qi + e;
-            pr = (!kvalid || (p.causal && kvrow > qrow)) ? 0.f : pr;
-            s0[j] = pr;
-            dp0[j] = pr * (dp0[j] - D4[e]);
-          }
-        }
-        phase_c(qb, s0, dp0);
-        write_ds(qb, dp0);
+      for (int ks = 0; ks < 8; ++ks) {
+        const int off = a_base + qb * 32 * kRowBytes + ks * 32;
+        s[qb] = mfma32(lds_read_b128(Qs, off), kT[ks], s[qb]);
+        dp[qb] = mfma32(lds_read_b128(Gs, off), vT[ks], dp[qb]);
       }
     }
+    // P and dS (in place: s <- P, dp <- dS)
+    const bool need_mask = (k0 + BN > p.s_k) || (p.causal && q0 < k0 + BN - 1);
+#pragma unroll
+    for (int qb = 0; qb < 2; ++qb)
+#pragma unroll
+      for (int g4 = 0; g4 < 4; ++g4) {
+        const int qi = qb * 32 + g4 * 8 + hh * 4;       // first of 4 consecutive query rows
+        const f32x4 L4 = *reinterpret_cast<const f32x4*>(LDs + qi);
+        const f32x4 D4 = *reinterpret_cast<const f32x4*>(LDs + 64 + qi);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          const int j = g4 * 4 + e;
+          float pr = __builtin_amdgcn_exp2f(fmaf(s[qb][j], c2, -L4[e]));
+          if (need_mask) {
+            const int qrow = q0 + qi + e;
+            if (!kvalid || (p.causal && kvrow > qrow)) pr = 0.f;
+          }
+          s[qb][j] = pr;
+          dp[qb][j] = pr * (dp[qb][j] - D4[e]);
+        }
+      }
+    // dV^T += dO^T P ; dK^T += Q^T dS
+#pragma unroll
+    for (int qb = 0; qb < 2; ++qb)
+#pragma unroll
+      for (int u = 0; u < 2; ++u) {
+        const bf16x8 pb = pack8(s[qb], u * 8);
+        const bf16x8 db_ = pack8(dp[qb], u * 8);
+#pragma unroll
+        for (int db = 0; db < 4; ++db) {
+          const int goff = g_base + (qb * 32 + u * 16) * kRowBytes + db * 64;
+          dvT[db] = mfma32(lds_gather(Gs, goff), pb, dvT[db]);
+          dkT[db] = mfma32(lds_gather(Qs, goff), db_, dkT[db]);
+        }
+      }
+    // dS^T -> LDS (8-byte pieces: 4 consecutive queries of this lane's key)
+#pragma unroll
+    for (int qb = 0; qb < 2; ++qb)
+#pragma unroll
+      for (int g4 = 0; g4 < 4; ++g4) {
+        bf16x4 b;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) b[e] = static_cast<__bf16>(dp[qb][g4 * 4 + e]);
+        *reinterpret_cast<bf16x4*>(Ts + w_base + (qb * 32 + g4 * 8) * 2) = b;
+      }
     __syncthreads();
     if (more) qtile_store(tr, Qs, Gs, LDs, tid);
-    {
-      f32x16 dq0, dq1;
-      dq_block(0, dq0);
-      dq_block(1, dq1);
-      float* dst = p.dq + hq * p.dq_sh + static_cast<int64_t>(q0) * p.dq_ss + wave * 32 + r32;
-      if (q0 + BM <= p.s_q) {
+    // dQ block (32 queries x this wavefront's 32 columns) over all 128 keys, then atomics
 #pragma unroll
-        for (int j = 0; j < 16; ++j) {
-          const int rr = (j >> 2) * 8 + hh * 4 + (j & 3);
-          atomicAdd(dst + static_cast<int64_t>(rr) * p.dq_ss, dq0[j] * p.scale);
-          atomicAdd(dst + static_cast<int64_t>(rr + 32) * p.dq_ss, dq1[j] * p.scale);
-        }
-      } else {
+    for (int qb = 0; qb < 2; ++qb) {
+      f32x16 dq;
 #pragma unroll
-        for (int j = 0; j < 16; ++j) {
-          const int rr = (j >> 2) * 8 + hh * 4 + (j & 3);
-          if (q0 + rr < p.s_q) atomicAdd(dst + static_cast<int64_t>(rr) * p.dq_ss, dq0[j] * p.scale);
-          if (q0 + rr + 32 < p.s_q) atomicAdd(dst + static_cast<int64_t>(rr + 32) * p.dq_ss, dq1[j] * p.scale);
-        }
+      for (int j = 0; j < 16; ++j) dq[j] = 0.f;
+#pragma unroll
+      for (int ks = 0; ks < 8; ++ks) {
+        // keys +16 per step = logical rows +8: physical +16 rows on even steps, +2 more on odd
+        // ones; the second half of the operand (keys +8) sits one physical row further
+        const int off = t_base + ((ks >> 1) * 16 + (ks & 1) * 2) * kRowBytes + qb * 64;
+        dq = mfma32(cat8(lds_read_tr(Ts, off), lds_read_tr(Ts, off + kRowBytes)), kB[ks], dq);
+      }
+      float* dst = p.dq + hq * p.dq_sh + wave * 32 + r32;
+#pragma unroll
+      for (int j = 0; j < 16; ++j) {
+        const int qrow = q0 + qb * 32 + (j >> 2) * 8 + hh * 4 + (j & 3);
+        if (qrow < p.s_q) atomicAdd(dst + static_cast<int64_t>(qrow) * p.dq_ss, dq[j] * p.scale);
       }
     }
     __syncthreads();

@@ -55,6 +55,13 @@ __device__ __forceinline__ void mfma_v_va(f32x16& acc, bf16x8 a, bf16x8 b) {
 __device__ __forceinline__ void mfma_v_va_last(f32x16& acc, bf16x8 a, bf16x8 b) {
   asm("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0\n\ts_nop 15" : "+v"(acc) : "v"(a), "a"(b));
 }
+// Last step of two chains at once (the compiler may reorder independent asm statements, so
+// the wait states have to sit in the same statement as BOTH final MFMAs).
+__device__ __forceinline__ void mfma2_v_va_last(f32x16& acc0, bf16x8 a0, bf16x8 b0,
+                                                f32x16& acc1, bf16x8 a1, bf16x8 b1) {
+  asm("v_mfma_f32_32x32x16_bf16 %0, %2, %3, %0\n\tv_mfma_f32_32x32x16_bf16 %1, %4, %5, %1\n\ts_nop 15"
+      : "+v"(acc0), "+v"(acc1) : "v"(a0), "a"(b0), "v"(a1), "a"(b1));
+}
 __device__ __forceinline__ void mfma_vz_vv(f32x16& acc, bf16x8 a, bf16x8 b) {
   asm("v_mfma_f32_32x32x16_bf16 %0, %1, %2, 0" : "=&v"(acc) : "v"(a), "v"(b));
 }
