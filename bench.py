@@ -35,7 +35,7 @@ def parse():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--config", type=int, default=1, help="index into dfa_inputs.CONFIGS (1 = the metric's workload)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--cpu-heads", type=int, default=2, help="heads of the share the oracle is timed on")
+    ap.add_argument("--cpu-heads", type=int, default=16, help="heads of the share the oracle is timed on")
     return ap.parse_args()
 
 
