@@ -119,8 +119,8 @@ int dfa_delta(const dfa_shape* sh, const void* o, const void* dO, float* delta, 
  *   delta : D from dfa_delta on the FINAL merged output (same for every pair of the chunk)
  *   dq [h_q,s_q,d], dk, dv [h_kv,s_k,d] : fp32.  accumulate == 0 overwrites them,
  *   accumulate != 0 adds this pair's contribution to what they hold.
- * dq is accumulated with fp32 atomics in the bf16 path, so its rounding order (not its
- * value beyond rounding) can differ between runs.
+ * The bf16 path runs two kernels (dk/dv, then dq) and is deterministic; the fp32 path adds dq
+ * with fp32 atomics, so its rounding order (not its value beyond rounding) can differ between runs.
  */
 int dfa_chunk_bwd(const dfa_shape* sh, const void* q, const void* k, const void* v,
                   const float* lse, const float* delta, const void* dO,
