@@ -110,7 +110,8 @@ __global__ void __launch_bounds__(NTHREADS, 1) k_bwd_dkdv_bf16(BwdParams p) {
   const int tk = item % p.ntile;     // causal: low key tiles meet the most query tiles and come first
   const int k0 = tk * BN;
 
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform: keeps tile branches scalar
   const int r32 = lane & 31, hh = lane >> 5;
   const int kvrow = k0 + wave * 32 + r32;
   const bool kvalid = kvrow < p.s_k;
@@ -161,84 +162,107 @@ __global__ void __launch_bounds__(NTHREADS, 1) k_bwd_dkdv_bf16(BwdParams p) {
     char* Qn = smem + (BUF_BYTES - boff);              // buffer of the next tile
     const bool edge = k_edge || (q0 + BM > p.s_q) || (p.causal && q0 < k0 + BN - 1);
 
+    // The tile is two blocks of 32 queries, software-pipelined by hand inside the wavefront (one
+    // wavefront per SIMD here, so nothing else hides latencies): the MFMAs of one block are
+    // issued between slices of the exp/VALU work of the other, and every LDS operand is read
+    // 2-4 MFMA steps before it is used.  DFA_SCHED_FENCE pins that order.
+#define DFA_RA(QB, KS, SL)                                                         \
+  {                                                                                \
+    const int off_ = a_base + (QB) * 32 * kRowBytes + (KS) * 32;                   \
+    qa[SL] = lds_read_b128(Qs, off_);                                              \
+    ga[SL] = lds_read_b128(Gs, off_);                                              \
+  }
+#define DFA_RG(QB, I, SL)                                                          \
+  {                                                                                \
+    const int off_ = g_base + ((QB) * 32 + ((I) >> 2) * 16) * kRowBytes + ((I) & 3) * 64; \
+    gd[SL] = lds_gather(Gs, off_);                                                 \
+    gq[SL] = lds_gather(Qs, off_);                                                 \
+  }
+#define DFA_RLD(QB, G4, SL)                                                        \
+  {                                                                                \
+    L4[SL] = *reinterpret_cast<const f32x4*>(LDs + (QB) * 32 + (G4) * 8 + hh * 4); \
+    D4[SL] = *reinterpret_cast<const f32x4*>(LDs + 64 + (QB) * 32 + (G4) * 8 + hh * 4); \
+  }
+#define DFA_BELEM(S, DP, QB, J)                                                    \
+  {                                                                                \
+    float pr_ = __builtin_amdgcn_exp2f(fmaf(S[J], c2, -L4[((J) >> 2) & 1][(J) & 3])); \
+    if (edge) {                                                                    \
+      const int qrow_ = q0 + (QB) * 32 + ((J) >> 2) * 8 + hh * 4 + ((J) & 3);       \
+      pr_ = (!kvalid || (p.causal && kvrow > qrow_)) ? 0.f : pr_;                  \
+    }                                                                              \
+    S[J] = pr_;                                                                    \
+    DP[J] = pr_ * (DP[J] - D4[((J) >> 2) & 1][(J) & 3]);                           \
+  }
+    {
+      bf16x8 qa[4], ga[4], gd[2], gq[2], pb0[2], sb0[2], pb1[2], sb1[2];
+      f32x4 L4[2], D4[2];
+      f32x16 s0, dp0, s1, dp1;
 #pragma unroll
-    for (int qb = 0; qb < 2; ++qb) {
-      // ---- S = Q K^T, dP = dO V^T for 32 queries: operand reads run 4 steps ahead of the MFMAs
-      bf16x8 qa[4], ga[4];
-      f32x16 s, dp;
+      for (int j = 0; j < 16; ++j) { s0[j] = 0.f; dp0[j] = 0.f; s1[j] = 0.f; dp1[j] = 0.f; }
 #pragma unroll
-      for (int j = 0; j < 16; ++j) { s[j] = 0.f; dp[j] = 0.f; }
-#pragma unroll
-      for (int ks = 0; ks < 4; ++ks) {
-        const int off = a_base + qb * 32 * kRowBytes + ks * 32;
-        qa[ks] = lds_read_b128(Qs, off);
-        ga[ks] = lds_read_b128(Gs, off);
-      }
-      if (qb == 0 && more) {   // global loads of the next tile; stored to the other buffer below
+      for (int ks = 0; ks < 4; ++ks) DFA_RA(0, ks, ks)
+      DFA_RLD(0, 0, 0)
+      if (more) {   // global loads of the next tile; stored to the other LDS buffer after the tile
         const int hq_n = kh * p.group + (it + 1) / ntq;
         const int q0_n = q_begin + ((it + 1) % ntq) * BM;
         if (q0_n + BM <= p.s_q) qtile_load<false>(tr, p, hq_n, q0_n, tid);
         else qtile_load<true>(tr, p, hq_n, q0_n, tid);
       }
       DFA_SCHED_FENCE();
+      // stage 1: S, dP of block 0
 #pragma unroll
       for (int ks = 0; ks < 8; ++ks) {
-        s = mfma32(qa[ks & 3], kT[ks], s);
-        dp = mfma32(ga[ks & 3], vT[ks], dp);
-        if (ks < 4) {
-          const int off = a_base + qb * 32 * kRowBytes + (ks + 4) * 32;
-          qa[ks & 3] = lds_read_b128(Qs, off);
-          ga[ks & 3] = lds_read_b128(Gs, off);
-        }
+        s0 = mfma32(qa[ks & 3], kT[ks], s0);
+        dp0 = mfma32(ga[ks & 3], vT[ks], dp0);
+        if (ks < 4) DFA_RA(0, ks + 4, ks & 3) else DFA_RA(1, ks - 4, ks & 3)
         DFA_SCHED_FENCE();
       }
-      // ---- P = exp2(S c - lse'), dS = P o (dP - D), in place
-      const int qi0 = qb * 32 + hh * 4;
+      // stage 2: S, dP of block 1 between slices of P, dS of block 0
 #pragma unroll
-      for (int g4 = 0; g4 < 4; ++g4) {
-        const f32x4 Lq = *reinterpret_cast<const f32x4*>(LDs + qi0 + g4 * 8);
-        const f32x4 Dq = *reinterpret_cast<const f32x4*>(LDs + 64 + qi0 + g4 * 8);
-#pragma unroll
-        for (int e = 0; e < 4; ++e) {
-          const int j = g4 * 4 + e;
-          const float pr = __builtin_amdgcn_exp2f(fmaf(s[j], c2, -Lq[e]));
-          s[j] = pr;
-          dp[j] = pr * (dp[j] - Dq[e]);
-        }
+      for (int ks = 0; ks < 8; ++ks) {
+        s1 = mfma32(qa[ks & 3], kT[ks], s1);
+        dp1 = mfma32(ga[ks & 3], vT[ks], dp1);
+        if (ks < 4) DFA_RA(1, ks + 4, ks & 3)
+        if (ks == 4) DFA_RG(0, 0, 0)
+        if (ks == 5) DFA_RG(0, 1, 1)
+        if ((ks & 1) == 0 && ks < 6) DFA_RLD(0, ks / 2 + 1, (ks / 2 + 1) & 1)
+        if (ks == 6) DFA_RLD(1, 0, 0)
+        DFA_BELEM(s0, dp0, 0, 2 * ks)
+        DFA_BELEM(s0, dp0, 0, 2 * ks + 1)
+        if (ks == 4) pb0[0] = pack8(s0, 0);
+        if (ks == 5) sb0[0] = pack8(dp0, 0);
+        DFA_SCHED_FENCE();
       }
-      if (edge) {   // causal diagonal / ragged key tail: zero the masked entries
-#pragma unroll
-        for (int j = 0; j < 16; ++j) {
-          const int qrow = q0 + qi0 + (j >> 2) * 8 + (j & 3);
-          const bool dead = !kvalid || (p.causal && kvrow > qrow);
-          s[j] = dead ? 0.f : s[j];
-          dp[j] = dead ? 0.f : dp[j];
-        }
-      }
-      // ---- dV^T += dO^T P, dK^T += Q^T dS: gathers run 2 steps ahead of the MFMAs
-      bf16x8 pb[2], sb[2], gd[2], gq[2];
-      pb[0] = pack8(s, 0); sb[0] = pack8(dp, 0);
-      pb[1] = pack8(s, 8); sb[1] = pack8(dp, 8);
-#pragma unroll
-      for (int i = 0; i < 2; ++i) {
-        const int goff = g_base + (qb * 32) * kRowBytes + i * 64;
-        gd[i] = lds_gather(Gs, goff);
-        gq[i] = lds_gather(Qs, goff);
-      }
-      DFA_SCHED_FENCE();
+      // stage 3: dV^T, dK^T of block 0 between slices of P, dS of block 1
 #pragma unroll
       for (int i = 0; i < 8; ++i) {
-        const int u = i >> 2, db = i & 3;
-        dvT[db] = mfma32(gd[i & 1], pb[u], dvT[db]);
-        dkT[db] = mfma32(gq[i & 1], sb[u], dkT[db]);
-        if (i + 2 < 8) {
-          const int goff = g_base + (qb * 32 + ((i + 2) >> 2) * 16) * kRowBytes + ((i + 2) & 3) * 64;
-          gd[i & 1] = lds_gather(Gs, goff);
-          gq[i & 1] = lds_gather(Qs, goff);
-        }
+        if (i == 0) pb0[1] = pack8(s0, 8);       // first used at i == 4
+        if (i == 1) sb0[1] = pack8(dp0, 8);
+        dvT[i & 3] = mfma32(gd[i & 1], pb0[i >> 2], dvT[i & 3]);
+        dkT[i & 3] = mfma32(gq[i & 1], sb0[i >> 2], dkT[i & 3]);
+        if (i + 2 < 8) DFA_RG(0, i + 2, i & 1) else DFA_RG(1, i - 6, i & 1)
+        if ((i & 1) == 0 && i < 6) DFA_RLD(1, i / 2 + 1, (i / 2 + 1) & 1)
+        DFA_BELEM(s1, dp1, 1, 2 * i)
+        DFA_BELEM(s1, dp1, 1, 2 * i + 1)
+        if (i == 4) pb1[0] = pack8(s1, 0);
+        if (i == 5) sb1[0] = pack8(dp1, 0);
+        DFA_SCHED_FENCE();
+      }
+      // stage 4: dV^T, dK^T of block 1
+#pragma unroll
+      for (int i = 0; i < 8; ++i) {
+        if (i == 0) pb1[1] = pack8(s1, 8);
+        if (i == 1) sb1[1] = pack8(dp1, 8);
+        dvT[i & 3] = mfma32(gd[i & 1], pb1[i >> 2], dvT[i & 3]);
+        dkT[i & 3] = mfma32(gq[i & 1], sb1[i >> 2], dkT[i & 3]);
+        if (i + 2 < 8) DFA_RG(1, i + 2, i & 1)
         DFA_SCHED_FENCE();
       }
     }
+#undef DFA_RA
+#undef DFA_RG
+#undef DFA_RLD
+#undef DFA_BELEM
     if (more) qtile_store(tr, Qn, Qn + QTILE_BYTES, reinterpret_cast<float*>(Qn + 2 * QTILE_BYTES), tid);
     __syncthreads();
   }
@@ -321,7 +345,8 @@ __global__ void __launch_bounds__(NTHREADS, 2) k_bwd_dq_bf16(BwdParams p) {
   const int kh = head / p.group;
   const int q0 = tq * BM;
 
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform: keeps tile branches scalar
   const int r32 = lane & 31, hh = lane >> 5;
   const int q0w = q0 + wave * 32;
   const int qrow = q0w + r32;

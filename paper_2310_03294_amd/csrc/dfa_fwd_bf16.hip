@@ -62,9 +62,7 @@ __device__ __forceinline__ void tile_store(const TileRegs& t, char* Ks, char* Vs
 }
 
 __global__ void __launch_bounds__(NTHREADS, 2) k_fwd_bf16(FwdParams p) {
-  extern __shared__ __align__(16) char smem[];
-  char* Ks = smem;
-  char* Vs = smem + TILE_BYTES;
+  extern __shared__ __align__(16) char smem[];   // two (K tile, V tile) buffers
 
   // XCD-aware mapping: consecutive workgroup ids go round-robin over the 8 XCDs, so give every
   // XCD a contiguous range of (head, query tile) items; its workgroups then share K/V in its L2.
@@ -77,7 +75,8 @@ __global__ void __launch_bounds__(NTHREADS, 2) k_fwd_bf16(FwdParams p) {
   const int kh = head / p.group;
   const int q0 = tq * BM;
 
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform: keeps tile branches scalar
   const int r32 = lane & 31, hh = lane >> 5;
   const int q0w = q0 + wave * 32;
   const int qrow = q0w + r32;
@@ -114,78 +113,142 @@ __global__ void __launch_bounds__(NTHREADS, 2) k_fwd_bf16(FwdParams p) {
 
   TileRegs tr;
   tile_load(tr, kg, vg, p.kv_ss, 0, p.s_k, tid);
-  tile_store(tr, Ks, Vs, tid);
+  tile_store(tr, smem, smem + TILE_BYTES, tid);
   __syncthreads();
+
+  // Online softmax of one 32-key block (exp2 domain, scores scaled by scale*log2 e), with a lazy
+  // running maximum: the reference maximum m_run only moves when some row's block maximum exceeds
+  // it by more than 2^8 in the exp2 domain (or on the first block).  Until then exponentials are
+  // taken against the stale maximum - they stay below 2^8, harmless in fp32 / bf16 - and O needs
+  // no rescaling; the final division by the row sum makes the result independent of the reference.
+  // Returns the factor O has to be multiplied by (1 when the reference did not move).
+  auto softmax_block = [&](f32x16& s) {
+    float mx = fmaxf(fmaxf(s[0], s[1]), s[2]);
+#pragma unroll
+    for (int j = 3; j < 15; j += 2) mx = fmaxf(fmaxf(mx, s[j]), s[j + 1]);
+    mx = fmaxf(mx, s[15]);
+    float alpha = 1.f;
+    if (__any((mx - m_run) * c2 > 8.f)) {          // -inf reference (first block) also lands here
+      mx = fmaxf(mx, __shfl_xor(mx, 32));
+      const float m_new = fmaxf(m_run, mx);
+      const float mc_new = (m_new == -INFINITY) ? 0.f : m_new * c2;
+      alpha = __builtin_amdgcn_exp2f(m_run * c2 - mc_new);
+      m_run = m_new;
+      l_run *= alpha;
+    }
+    const float mc = (m_run == -INFINITY) ? 0.f : m_run * c2;
+    float sum = 0.f;
+#pragma unroll
+    for (int j = 0; j < 16; ++j) {
+      const float e = __builtin_amdgcn_exp2f(fmaf(s[j], c2, -mc));
+      s[j] = e;
+      sum += e;
+    }
+    l_run += sum;
+    return alpha;
+  };
+  auto rescale_o = [&](float alpha) {
+    if (__any(alpha != 1.f)) {
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 16; ++j) o[i][j] *= alpha;
+    }
+  };
+  auto mask_block = [&](f32x16& s, int kbase) {
+#pragma unroll
+    for (int j = 0; j < 16; ++j) {
+      const int kvi = kbase + (j >> 2) * 8 + hh * 4 + (j & 3);
+      if (kvi >= p.s_k || (p.causal && kvi > qrow)) s[j] = -INFINITY;
+    }
+  };
 
   for (int it = 0; it < ntiles; ++it) {
     const int k0 = it * BN;
     const bool more = it + 1 < ntiles;
+    const int boff = (it & 1) * 2 * TILE_BYTES;
+    const char* Ks = smem + boff;
+    const char* Vs = Ks + TILE_BYTES;
+    char* Kn = smem + (2 * TILE_BYTES - boff);
     if (more) tile_load(tr, kg, vg, p.kv_ss, k0 + BN, p.s_k, tid);
 
     const bool active = !(p.causal && k0 > q0w + 31);
     if (active) {
-      // S^T = K Q^T : two 32-key blocks
-      f32x16 s[2];
+      const bool need_mask = (k0 + BN > p.s_k) || (p.causal && k0 + BN - 1 > q0w);
+      // Software pipeline over the two 32-key blocks of the tile: the MFMAs of one block run
+      // under the softmax arithmetic of the other; LDS operand reads run ahead of their MFMAs.
+      bf16x8 ka[4], gv[2], pb0[2], pb1[2];
+      f32x16 s0, s1;
 #pragma unroll
-      for (int nb = 0; nb < 2; ++nb) {
+      for (int j = 0; j < 16; ++j) { s0[j] = 0.f; s1[j] = 0.f; }
 #pragma unroll
-        for (int j = 0; j < 16; ++j) s[nb][j] = 0.f;
+      for (int ks = 0; ks < 4; ++ks) ka[ks] = lds_read_b128(Ks, a_base + ks * 32);
+      DFA_SCHED_FENCE();
+      // stage 1: S0^T = K0 Q^T
+#pragma unroll
+      for (int ks = 0; ks < 8; ++ks) {
+        s0 = mfma32(ka[ks & 3], qreg[ks], s0);
+        ka[ks & 3] = lds_read_b128(Ks, ks < 4 ? a_base + (ks + 4) * 32 : a_base + 32 * kRowBytes + (ks - 4) * 32);
+        DFA_SCHED_FENCE();
+      }
+      if (need_mask) mask_block(s0, k0);
+      DFA_SCHED_FENCE();
+      // stage 2: S1^T = K1 Q^T  ||  softmax of block 0
+      float alpha0;
+      {
 #pragma unroll
         for (int ks = 0; ks < 8; ++ks) {
-          const bf16x8 a = lds_read_b128(Ks, a_base + nb * 32 * kRowBytes + ks * 32);
-          s[nb] = mfma32(a, qreg[ks], s[nb]);
+          s1 = mfma32(ka[ks & 3], qreg[ks], s1);
+          if (ks < 4) ka[ks & 3] = lds_read_b128(Ks, a_base + 32 * kRowBytes + (ks + 4) * 32);
+        }
+        gv[0] = lds_gather(Vs, g_base);
+        gv[1] = lds_gather(Vs, g_base + 64);
+        alpha0 = softmax_block(s0);
+        pb0[0] = pack8(s0, 0); pb0[1] = pack8(s0, 8);
+#pragma unroll
+        for (int r = 0; r < 8; ++r) {
+          __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);   // 1 MFMA
+          __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);   // 1 LDS read
+          __builtin_amdgcn_sched_group_barrier(0x002, 9, 0);   // 9 VALU
         }
       }
-      const bool need_mask = (k0 + BN > p.s_k) || (p.causal && k0 + BN - 1 > q0w);
-      if (need_mask) {
+      DFA_SCHED_FENCE();
+      rescale_o(alpha0);
+      if (need_mask) mask_block(s1, k0 + 32);
+      DFA_SCHED_FENCE();
+      // stage 3: O^T += V0^T P0^T  ||  softmax of block 1
+      float alpha1;
+      {
 #pragma unroll
-        for (int nb = 0; nb < 2; ++nb)
-#pragma unroll
-          for (int j = 0; j < 16; ++j) {
-            const int kv = k0 + nb * 32 + (j >> 2) * 8 + hh * 4 + (j & 3);
-            if (kv >= p.s_k || (p.causal && kv > qrow)) s[nb][j] = -INFINITY;
-          }
-      }
-      // online softmax in the exp2 domain (scores scaled by scale*log2 e)
-      float mx = s[0][0];
-#pragma unroll
-      for (int j = 1; j < 16; ++j) mx = fmaxf(mx, s[0][j]);
-#pragma unroll
-      for (int j = 0; j < 16; ++j) mx = fmaxf(mx, s[1][j]);
-      mx = fmaxf(mx, __shfl_xor(mx, 32));
-      const float m_new = fmaxf(m_run, mx);
-      const float mc = (m_new == -INFINITY) ? 0.f : m_new * c2;
-      const float alpha = __builtin_amdgcn_exp2f(m_run * c2 - mc);
-      float sum = 0.f;
-#pragma unroll
-      for (int nb = 0; nb < 2; ++nb)
-#pragma unroll
-        for (int j = 0; j < 16; ++j) {
-          const float e = __builtin_amdgcn_exp2f(fmaf(s[nb][j], c2, -mc));
-          s[nb][j] = e;
-          sum += e;
+        for (int i = 0; i < 8; ++i) {
+          o[i & 3] = mfma32(gv[i & 1], pb0[i >> 2], o[i & 3]);
+          const int n = i + 2;    // next gather: block 0 second half, then block 1
+          gv[i & 1] = lds_gather(Vs, g_base + (n >> 2) * 16 * kRowBytes + (n & 3) * 64);
         }
-      l_run = l_run * alpha + sum;
-      m_run = m_new;
-      if (!__all(alpha == 1.f)) {
+        alpha1 = softmax_block(s1);
+        pb1[0] = pack8(s1, 0); pb1[1] = pack8(s1, 8);
 #pragma unroll
-        for (int i = 0; i < 4; ++i)
-#pragma unroll
-          for (int j = 0; j < 16; ++j) o[i][j] *= alpha;
-      }
-      // O^T += V^T P^T : 4 contraction steps of 16 keys, 4 blocks of 32 output columns
-#pragma unroll
-      for (int kk = 0; kk < 4; ++kk) {
-        const bf16x8 pb = pack8(s[kk >> 1], (kk & 1) * 8);
-#pragma unroll
-        for (int db = 0; db < 4; ++db) {
-          const bf16x8 a = lds_gather(Vs, g_base + kk * 16 * kRowBytes + db * 64);
-          o[db] = mfma32(a, pb, o[db]);
+        for (int r = 0; r < 8; ++r) {
+          __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+          __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
+          __builtin_amdgcn_sched_group_barrier(0x002, 9, 0);
         }
+      }
+      DFA_SCHED_FENCE();
+      rescale_o(alpha1);
+      DFA_SCHED_FENCE();
+      // stage 4: O^T += V1^T P1^T
+#pragma unroll
+      for (int i = 0; i < 8; ++i) {
+        o[i & 3] = mfma32(gv[i & 1], pb1[i >> 2], o[i & 3]);
+        if (i + 2 < 8) {
+          const int n = i + 10;
+          gv[i & 1] = lds_gather(Vs, g_base + (n >> 2) * 16 * kRowBytes + (n & 3) * 64);
+        }
+        DFA_SCHED_FENCE();
       }
     }
-    __syncthreads();
-    if (more) tile_store(tr, Ks, Vs, tid);
+    if (more) tile_store(tr, Kn, Kn + TILE_BYTES, tid);
     __syncthreads();
   }
 
@@ -229,7 +292,15 @@ int launch_fwd_bf16(const dfa_shape& sh, const void* q, const void* k, const voi
   if (total > (1 << 30)) return DFA_ERR_SHAPE;
   p.total = static_cast<int>(total);
   p.per_xcd = (p.total + 7) / 8;
-  k_fwd_bf16<<<p.per_xcd * 8, NTHREADS, 2 * TILE_BYTES, st>>>(p);
+  const size_t smem = 4 * TILE_BYTES;     // two (K, V) buffers; above 64 KB needs the opt-in once
+  static bool attr_set = false;
+  if (!attr_set) {
+    const int rc = hip_status(hipFuncSetAttribute(reinterpret_cast<const void*>(k_fwd_bf16),
+                                                  hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(smem)));
+    if (rc) return rc;
+    attr_set = true;
+  }
+  k_fwd_bf16<<<p.per_xcd * 8, NTHREADS, smem, st>>>(p);
   return last_launch_status();
 }
 
