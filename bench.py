@@ -121,22 +121,36 @@ def main():
     def chunk(t, i):
         return t[:, i * c:(i + 1) * c]
 
-    ev_bwd = []     # (start, end, flops) per backward-kernel launch inside the timed region
+    # HIP events on the stream the kernels run on (torch's current stream; the binding passes
+    # that stream to the library): one pair per backward kernel launch, one around the forward.
+    ev = {"k_bwd_dkdv_bf16": [], "k_bwd_dq_bf16": [], "forward": []}
+
+    def timed(name, record, flops, fn):
+        if not record:
+            fn()
+            return
+        e0 = torch.cuda.Event(enable_timing=True); e1 = torch.cuda.Event(enable_timing=True)
+        e0.record(); fn(); e1.record()
+        ev[name].append((e0, e1, flops))
+
+    fwd_flops = 4.0 * w.d * w.h_q * nnz
 
     def step(record):
-        driver.forward_worker(Q, K, V, w.scale, w.p, worker, bufs, remote=remote)
+        timed("forward", record, fwd_flops,
+              lambda: driver.forward_worker(Q, K, V, w.scale, w.p, worker, bufs, remote=remote))
         B.dfa_delta(chunk(bufs.O, worker), chunk(dO, worker), delta=chunk(bufs.delta, worker))
         for (qc, kc, kind) in pairs:
-            if record:
-                e0 = torch.cuda.Event(enable_timing=True); e1 = torch.cuda.Event(enable_timing=True)
-                e0.record()
-            B.dfa_chunk_bwd(chunk(Q, qc), chunk(K, kc), chunk(V, kc), chunk(bufs.L, qc), chunk(bufs.delta, qc),
-                            chunk(dO, qc), chunk(bufs.dQ, qc), chunk(bufs.dK, kc), chunk(bufs.dV, kc),
-                            kind == B.DFA_STEP_DIAG, w.scale, accumulate=True)
-            if record:
-                e1.record()
-                n = c * (c + 1) // 2 if qc == kc else c * c
-                ev_bwd.append((e0, e1, 10.0 * w.d * w.h_q * n))
+            n = c * (c + 1) // 2 if qc == kc else c * c
+            common = (chunk(Q, qc), chunk(K, kc), chunk(V, kc), chunk(bufs.L, qc), chunk(bufs.delta, qc), chunk(dO, qc))
+            diag = kind == B.DFA_STEP_DIAG
+            # the two kernels of one dfa_chunk_bwd, launched through the same entry point one at a
+            # time so that each gets its own event pair: S, dP, dV, dK = 8 d nnz; dQ (with S, dP
+            # recomputed) = 2 d nnz algorithmic, 6 d nnz executed
+            timed("k_bwd_dkdv_bf16", record, 8.0 * w.d * w.h_q * n,
+                  lambda: B.dfa_chunk_bwd(*common, None, chunk(bufs.dK, kc), chunk(bufs.dV, kc), diag, w.scale,
+                                          accumulate=True))
+            timed("k_bwd_dq_bf16", record, 2.0 * w.d * w.h_q * n,
+                  lambda: B.dfa_chunk_bwd(*common, chunk(bufs.dQ, qc), None, None, diag, w.scale, accumulate=True))
 
     for _ in range(args.warmup):
         step(False)
@@ -149,14 +163,28 @@ def main():
     ms = dt * 1e3 / args.steps
     tflops = flops_step / (ms * 1e-3) / 1e12
 
-    bwd_ms = sum(a.elapsed_time(b) for a, b, _ in ev_bwd)
-    bwd_fl = sum(f for _, _, f in ev_bwd)
-    achieved = bwd_fl / (bwd_ms * 1e-3) / 1e12
-    roofline = {"bound": "mfma", "kernel": "k_bwd_bf16", "achieved": round(achieved, 2), "peak": PEAK_BF16_TFLOPS,
-                "unit": "TFLOP/s", "frac": round(achieved / PEAK_BF16_TFLOPS, 4),
-                "avg_launch_ms": round(bwd_ms / len(ev_bwd), 4),
-                "flop_per_launch": bwd_fl / len(ev_bwd),
-                "traffic": traffic_from_profiles("k_bwd_bf16_cfg2_pmc.txt")}
+    def summary(name):
+        tot_ms = sum(a.elapsed_time(b) for a, b, _ in ev[name])
+        tot_fl = sum(f for _, _, f in ev[name])
+        return tot_ms, tot_fl, len(ev[name])
+
+    kv_ms, kv_fl, kv_n = summary("k_bwd_dkdv_bf16")
+    dq_ms, dq_fl, dq_n = summary("k_bwd_dq_bf16")
+    fw_ms, fw_fl, fw_n = summary("forward")
+    achieved = kv_fl / (kv_ms * 1e-3) / 1e12
+    roofline = {"bound": "mfma", "kernel": "k_bwd_dkdv_bf16", "achieved": round(achieved, 2),
+                "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": round(achieved / PEAK_BF16_TFLOPS, 4),
+                "avg_launch_ms": round(kv_ms / kv_n, 4), "flop_per_launch": kv_fl / kv_n,
+                "traffic": traffic_from_profiles("k_bwd_dkdv_bf16_cfg2_pmc.txt"),
+                "share_of_step": round(kv_ms / args.steps / ms, 3),
+                "others": {
+                    "k_bwd_dq_bf16": {"avg_launch_ms": round(dq_ms / dq_n, 4),
+                                      "algorithmic_tflops": round(dq_fl / (dq_ms * 1e-3) / 1e12, 2),
+                                      "executed_tflops": round(3.0 * dq_fl / (dq_ms * 1e-3) / 1e12, 2),
+                                      "share_of_step": round(dq_ms / args.steps / ms, 3)},
+                    "forward (k_fwd_bf16 x5 + k_merge x7)": {"ms_per_step": round(fw_ms / fw_n, 4),
+                                                            "tflops": round(fw_fl / (fw_ms * 1e-3) / 1e12, 2),
+                                                            "share_of_step": round(fw_ms / args.steps / ms, 3)}}}
 
     out = {
         "metric": "causal-adjusted attention TFLOP/s fwd+bwd per worker share; % of bf16 MFMA peak",

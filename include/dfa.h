@@ -42,7 +42,7 @@ typedef enum {
   DFA_ERR_SHAPE = -2,     /* sizes / strides / alignment the kernels cannot take */
   DFA_ERR_DTYPE = -3,     /* unknown or unsupported dtype combination */
   DFA_ERR_ARG = -4,       /* inconsistent arguments (e.g. causal with s_q != s_k) */
-  DFA_ERR_WORKSPACE = -5, /* workspace missing or smaller than dfa_workspace_bytes() */
+  DFA_ERR_WORKSPACE = -5, /* reserved: no entry point takes a workspace yet */
   DFA_ERR_HIP = -6        /* the HIP runtime refused a launch */
 } dfa_status;
 
@@ -119,6 +119,9 @@ int dfa_delta(const dfa_shape* sh, const void* o, const void* dO, float* delta, 
  *   delta : D from dfa_delta on the FINAL merged output (same for every pair of the chunk)
  *   dq [h_q,s_q,d], dk, dv [h_kv,s_k,d] : fp32.  accumulate == 0 overwrites them,
  *   accumulate != 0 adds this pair's contribution to what they hold.
+ *   A NULL output selects what is computed: dq == NULL gives dk, dv only; dk == dv == NULL
+ *   gives dq only (so a worker can send one while the other is still being computed); dk
+ *   and dv are given together; all three NULL is DFA_ERR_NULL.
  * The bf16 path runs two kernels (dk/dv, then dq) and is deterministic; the fp32 path adds dq
  * with fp32 atomics, so its rounding order (not its value beyond rounding) can differ between runs.
  */

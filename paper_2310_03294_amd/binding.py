@@ -190,22 +190,31 @@ def dfa_delta(o, dO, delta=None, stream=None):
 
 
 def dfa_chunk_bwd(q, k, v, lse, delta, dO, dq, dk, dv, causal, scale, accumulate=False, stream=None):
-    """dq, dk, dv contributions of one chunk pair from the saved logsumexp and D (no forward re-run)."""
+    """dq, dk, dv contributions of one chunk pair from the saved logsumexp and D (no forward re-run).
+    dq=None computes only dk, dv; dk=dv=None computes only dq."""
     lib = load_library()
     if v.shape != k.shape or v.stride() != k.stride():
         raise ValueError("k and v must share shape and strides")
     if dO.shape != q.shape or dO.stride() != q.stride():
         raise ValueError("dO and q must share shape and strides")
-    if dv.shape != dk.shape or dv.stride() != dk.stride():
+    if (dk is None) != (dv is None):
+        raise ValueError("dk and dv are given together or not at all")
+    if dq is None and dk is None:
+        raise ValueError("nothing to compute: dq, dk, dv are all None")
+    if dk is not None and (dv.shape != dk.shape or dv.stride() != dk.stride()):
         raise ValueError("dk and dv must share shape and strides")
     if lse.stride() != delta.stride():
         raise ValueError("lse and delta must share strides")
     for t in (dq, dk, dv, lse, delta):
-        if t.dtype != torch.float32:
+        if t is not None and t.dtype != torch.float32:
             raise TypeError("dq, dk, dv, lse, delta are fp32")
     sh = _make_shape(q, k, causal, scale, _dt(q), lse=lse, dq=dq, dkv=dk)
+
+    def ptr(t):
+        return None if t is None else t.data_ptr()
+
     _check(lib.dfa_chunk_bwd(ctypes.byref(sh), q.data_ptr(), k.data_ptr(), v.data_ptr(), lse.data_ptr(),
-                             delta.data_ptr(), dO.data_ptr(), dq.data_ptr(), dk.data_ptr(), dv.data_ptr(),
+                             delta.data_ptr(), dO.data_ptr(), ptr(dq), ptr(dk), ptr(dv),
                              int(bool(accumulate)), _stream(stream)), "dfa_chunk_bwd")
     return dq, dk, dv
 

@@ -102,7 +102,10 @@ extern "C" int dfa_chunk_bwd(const dfa_shape* sh, const void* q, const void* k, 
                              float* dq, float* dk, float* dv, int accumulate, void* stream) {
   int rc = check_common(sh);
   if (rc != DFA_OK) return rc;
-  if (!q || !k || !v || !lse || !delta || !dO || !dq || !dk || !dv) return DFA_ERR_NULL;
+  if (!q || !k || !v || !lse || !delta || !dO) return DFA_ERR_NULL;
+  // dq alone, (dk, dv) alone, or all three: a NULL output selects which gradients are computed
+  if ((dk == nullptr) != (dv == nullptr)) return DFA_ERR_NULL;
+  if (!dq && !dk) return DFA_ERR_NULL;
   if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(dO) || !aligned16(dq) ||
       !aligned16(dk) || !aligned16(dv))
     return DFA_ERR_SHAPE;
@@ -116,8 +119,8 @@ extern "C" int dfa_chunk_bwd(const dfa_shape* sh, const void* q, const void* k, 
   if (sh->s_q == 0 || sh->s_k == 0) {
     // nothing flows through an empty pair; honour "overwrite" semantics
     if (!accumulate) {
-      if (sh->s_q > 0) { rc = dfa::launch_fill_zero_rows(dq, sh->h_q, sh->s_q, sh->d, sh->dq_stride_h, sh->dq_stride_s, st); if (rc) return rc; }
-      if (sh->s_k > 0) {
+      if (sh->s_q > 0 && dq) { rc = dfa::launch_fill_zero_rows(dq, sh->h_q, sh->s_q, sh->d, sh->dq_stride_h, sh->dq_stride_s, st); if (rc) return rc; }
+      if (sh->s_k > 0 && dk) {
         rc = dfa::launch_fill_zero_rows(dk, sh->h_kv, sh->s_k, sh->d, sh->dkv_stride_h, sh->dkv_stride_s, st); if (rc) return rc;
         rc = dfa::launch_fill_zero_rows(dv, sh->h_kv, sh->s_k, sh->d, sh->dkv_stride_h, sh->dkv_stride_s, st); if (rc) return rc;
       }

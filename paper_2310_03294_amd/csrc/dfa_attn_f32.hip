@@ -241,7 +241,7 @@ __global__ void __launch_bounds__(kThreads) k_bwd_f32(F32Params p) {
 #pragma unroll
           for (int c = 0; c < NC; ++c) { dv[a][c] = fmaf(pj[a], gv[c], dv[a][c]); dk[a][c] = fmaf(tj[a], qv[c], dk[a][c]); }
       }
-      {  // dq_i += sum_j (scale dS_ij) k_j : row tid/8, cols (tid%8) + 8c
+      if (p.dq) {  // dq_i += sum_j (scale dS_ij) k_j : row tid/8, cols (tid%8) + 8c
         const int r = tid / 8, cx = tid % 8;
         float dqa[NQ];
 #pragma unroll
@@ -262,7 +262,7 @@ __global__ void __launch_bounds__(kThreads) k_bwd_f32(F32Params p) {
 #pragma unroll
   for (int a = 0; a < 4; ++a) {
     const int kj = k0 + ty * 4 + a;
-    if (kj >= p.s_k) continue;
+    if (kj >= p.s_k || !p.dk) continue;
     float* dkp = p.dk + kh * p.dkv_sh + static_cast<int64_t>(kj) * p.dkv_ss;
     float* dvp = p.dv + kh * p.dkv_sh + static_cast<int64_t>(kj) * p.dkv_ss;
 #pragma unroll
@@ -312,7 +312,7 @@ int launch_bwd_f32(const dfa_shape& sh, const float* q, const float* k, const fl
   p.q = q; p.k = k; p.v = v; p.lse_in = lse; p.delta = delta; p.dO = dO;
   p.dq = dq; p.dk = dk; p.dv = dv; p.accumulate = accumulate;
   int rc;
-  if (!accumulate) {
+  if (!accumulate && dq) {
     rc = launch_fill_zero_rows(dq, sh.h_q, sh.s_q, sh.d, sh.dq_stride_h, sh.dq_stride_s, st);
     if (rc) return rc;
   }

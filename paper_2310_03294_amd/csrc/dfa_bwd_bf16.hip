@@ -492,7 +492,7 @@ int launch_bwd_bf16(const dfa_shape& sh, const void* q, const void* k, const voi
   p.l_sh = sh.lse_stride_h; p.dq_sh = sh.dq_stride_h; p.dq_ss = sh.dq_stride_s;
   p.dkv_sh = sh.dkv_stride_h; p.dkv_ss = sh.dkv_stride_s;
 
-  {  // dK, dV
+  if (dk) {  // dK, dV
     BwdParams a = p;
     a.ntile = (sh.s_k + kv::BN - 1) / kv::BN;
     const int64_t total = static_cast<int64_t>(a.ntile) * sh.h_kv;
@@ -512,7 +512,7 @@ int launch_bwd_bf16(const dfa_shape& sh, const void* q, const void* k, const voi
     const int rc = last_launch_status();
     if (rc) return rc;
   }
-  {  // dQ
+  if (dq) {  // dQ
     BwdParams b = p;
     b.ntile = (sh.s_q + qs::BM - 1) / qs::BM;
     const int64_t total = static_cast<int64_t>(b.ntile) * sh.h_q;

@@ -95,6 +95,10 @@ def test_null_and_alignment_errors(lib):
     assert lib.dfa_chunk_fwd(ctypes.byref(sh), None, FAKE, FAKE, FAKE, FAKE, None) == -1
     assert lib.dfa_chunk_fwd(ctypes.byref(sh), FAKE + 4, FAKE, FAKE, FAKE, FAKE, None) == -2
     assert lib.dfa_chunk_bwd(ctypes.byref(sh), FAKE, FAKE, FAKE, FAKE, None, FAKE, FAKE, FAKE, FAKE, 0, None) == -1
+    # outputs: dq alone or (dk, dv) alone are allowed, anything else NULL is not
+    assert lib.dfa_chunk_bwd(ctypes.byref(sh), FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, None, None, None, 0, None) == -1
+    assert lib.dfa_chunk_bwd(ctypes.byref(sh), FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, None, FAKE, 0, None) == -1
+    assert lib.dfa_chunk_bwd(ctypes.byref(sh), FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, None, 0, None) == -1
     assert lib.dfa_chunk_bwd(ctypes.byref(_shape(dq_stride_s=8)), FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE,
                              FAKE, 0, None) == -2
     assert lib.dfa_delta(ctypes.byref(sh), FAKE, None, FAKE, None) == -1

@@ -81,6 +81,15 @@ def _run_pair(dtype, h_q, h_kv, s_q, s_k, d, causal, o_dtype=torch.float32):
     torch.cuda.synchronize()
     errs2 = dict(dq=maxerr(dq, 2 * rq), dk=maxerr(dk, 2 * rk), dv=maxerr(dv, 2 * rv))
     assert all(e <= 2 * tol for e in errs2.values()), errs2
+    # a NULL output selects the other gradients only: (dk, dv) alone, then dq alone
+    dq3 = torch.full_like(dq, 7.0); dk3 = torch.full_like(dk, 7.0); dv3 = torch.full_like(dv, 7.0)
+    dfa.dfa_chunk_bwd(Q, K, V, lse, delta, dO, None, dk3, dv3, causal, scale, accumulate=False)
+    torch.cuda.synchronize()
+    assert maxerr(dk3, rk) <= tol and maxerr(dv3, rv) <= tol and bool((dq3 == 7.0).all())
+    dk3.fill_(7.0); dv3.fill_(7.0)
+    dfa.dfa_chunk_bwd(Q, K, V, lse, delta, dO, dq3, None, None, causal, scale, accumulate=False)
+    torch.cuda.synchronize()
+    assert maxerr(dq3, rq) <= tol and bool((dk3 == 7.0).all()) and bool((dv3 == 7.0).all())
 
 
 @pytest.mark.parametrize("shape", SHAPES_F32)
