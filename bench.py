@@ -35,6 +35,9 @@ def parse():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--config", type=int, default=1, help="index into dfa_inputs.CONFIGS (1 = the metric's workload)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also launch one plain elementwise kernel that reads 1 GiB and writes 1 GiB, "
+                         "the known-size reference for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE readings")
     ap.add_argument("--cpu-heads", type=int, default=16, help="heads of the share the oracle is timed on")
     return ap.parse_args()
 
@@ -151,6 +154,14 @@ def main():
                                           accumulate=True))
             timed("k_bwd_dq_bf16", record, 2.0 * w.d * w.h_q * n,
                   lambda: B.dfa_chunk_bwd(*common, chunk(bufs.dQ, qc), None, None, diag, w.scale, accumulate=True))
+
+    if args.calibrate_copy:
+        src = torch.zeros(1 << 28, dtype=torch.float32, device=dev)
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        torch.add(src, 1.0, out=dst)     # one dispatch: 2^30 B read, 2^30 B written
+        torch.cuda.synchronize()
+        del src, dst
 
     for _ in range(args.warmup):
         step(False)
