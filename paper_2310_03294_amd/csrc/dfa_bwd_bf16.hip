@@ -3,15 +3,17 @@
 //
 // Two kernels, no atomics, deterministic:
 //
-//  k_bwd_dkdv_bf16 (key-stationary).  A workgroup of 4 wavefronts owns 128 key rows of one kv
-//  head (32 per wavefront, their K and V held in registers as MFMA B operands) and walks over the
-//  query heads of the group and their query tiles of 64 rows, staged (Q, dO, lse, D) in a
-//  double-buffered LDS tile.  Per tile and wavefront, on v_mfma_f32_32x32x16_bf16:
-//    S = Q K^T, dP = dO V^T         (queries x keys: each lane holds 16 queries of ONE key)
-//    P = exp2(S c - lse log2e), dS = P o (dP - D)          (registers only)
-//    dV^T += dO^T P, dK^T += Q^T dS (P, dS fed back from registers as B operands; dO^T, Q^T
-//                                    gathered from LDS with the transposing read)
-//  dk, dv are written once per workgroup (summed over the group's query heads in registers).
+//  k_bwd_dkdv_bf16 (key-stationary).  A workgroup of 8 wavefronts owns 128 key rows of one kv
+//  head and walks over the query heads of the group and their query tiles of 64 rows, staged
+//  (Q, dO, lse, D) through LDS rings.  The wavefronts are specialised in pairs per 32-key block,
+//  one of each kind per SIMD, so that the exponentials of one overlap the MFMAs of the other:
+//    "S" wavefront  (K^T in registers):  S = Q K^T, P = exp2(S c - lse log2e), hands P (bf16)
+//                                        to its partner through LDS, dV^T += dO^T P
+//    "dP" wavefront (V^T in registers):  dP = dO V^T, dS = P o (dP - D), dK^T += Q^T dS
+//  (queries x keys tiles on v_mfma_f32_32x32x16_bf16: each lane holds 16 queries of ONE key; P
+//  and dS are fed back from registers as B operands; dO^T, Q^T are gathered from LDS with the
+//  transposing read).  The dP wavefronts run one tile behind, so one barrier per tile suffices.
+//  dv / dk are written once per workgroup (summed over the group's query heads in registers).
 //
 //  k_bwd_dq_bf16 (query-stationary).  A workgroup of 4 wavefronts owns 128 query rows of one head
 //  (Q^T, dO^T, lse, D in registers) and walks over the key/value chunk in tiles of 64 rows in
@@ -45,12 +47,20 @@ struct BwdParams {
 // ============================================================================================
 namespace kv {
 
-constexpr int BN = 128;    // key rows per workgroup
-constexpr int BM = 64;     // query rows per LDS tile
-constexpr int QTILE_BYTES = BM * kRowBytes;        // rows padded to 272 B
-constexpr int BUF_BYTES = 2 * QTILE_BYTES + 512;   // Q tile, dO tile, lse'[64] + D[64]
+constexpr int NT = 512;     // 8 wavefronts: 4 "S" wavefronts (dV) and 4 "dP" wavefronts (dK)
+constexpr int BN = 128;     // key rows per workgroup, 32 per wavefront pair
+constexpr int BM = 64;      // query rows per LDS tile
+constexpr int QTILE_BYTES = BM * kRowBytes;   // rows padded to 272 B
+constexpr int LD_BYTES = 512;                 // lse'[64] then D[64]
+constexpr int PX_BYTES = 4 * 4096;            // P hand-over: 4 key blocks x (64 x 32 bf16)
+// LDS map.  Tile t lives in Q slot t % 3, dO slot t % 2, lse/D slot t % 3, P slot t % 2.
+constexpr int OFF_Q = 0;
+constexpr int OFF_G = OFF_Q + 3 * QTILE_BYTES;
+constexpr int OFF_LD = OFF_G + 2 * QTILE_BYTES;
+constexpr int OFF_PX = OFF_LD + 3 * LD_BYTES;
+constexpr int SMEM_BYTES = OFF_PX + 2 * PX_BYTES;
 
-struct QTileRegs { uint4 q[4], g[4]; float ld; };
+struct QTileRegs { uint4 q[2], g[2]; float ld; };
 
 template <bool EDGE>
 __device__ __forceinline__ void qtile_load(QTileRegs& t, const BwdParams& p, int hq, int q0, int tid) {
@@ -58,8 +68,8 @@ __device__ __forceinline__ void qtile_load(QTileRegs& t, const BwdParams& p, int
   const __bf16* qg = p.q + hq * p.q_sh;
   const __bf16* gg = p.dO + hq * p.q_sh;
 #pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    const int r = (tid >> 4) + 16 * i;
+  for (int i = 0; i < 2; ++i) {
+    const int r = (tid >> 4) + 32 * i;
     if (!EDGE || q0 + r < p.s_q) {
       const int64_t off = static_cast<int64_t>(q0 + r) * p.q_ss + c * 8;
       t.q[i] = *reinterpret_cast<const uint4*>(qg + off);
@@ -88,8 +98,8 @@ __device__ __forceinline__ void qtile_load(QTileRegs& t, const BwdParams& p, int
 __device__ __forceinline__ void qtile_store(const QTileRegs& t, char* Qs, char* Gs, float* LDs, int tid) {
   const int c = tid & 15;
 #pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    const int r = (tid >> 4) + 16 * i;
+  for (int i = 0; i < 2; ++i) {
+    const int r = (tid >> 4) + 32 * i;
     const int off = tile_off(r, c);
     *reinterpret_cast<uint4*>(Qs + off) = t.q[i];
     *reinterpret_cast<uint4*>(Gs + off) = t.g[i];
@@ -97,9 +107,56 @@ __device__ __forceinline__ void qtile_store(const QTileRegs& t, char* Qs, char* 
   if (tid < 128) LDs[tid] = t.ld;
 }
 
-__global__ void __launch_bounds__(NTHREADS, 1) k_bwd_dkdv_bf16(BwdParams p) {
+// C[qb] = X[qb rows] * B^T over d for both 32-row blocks of the tile: X rows are read from LDS
+// (A operand), B is the wavefront's K^T or V^T held in registers.
+__device__ __forceinline__ void row_products(f32x16& c0, f32x16& c1, const char* Xs, int a_base,
+                                             const bf16x8 (&bT)[8]) {
+  constexpr int AHEAD = 3;                      // LDS reads run this many d-steps ahead of the MFMAs
+  bf16x8 x0[AHEAD + 1], x1[AHEAD + 1];
+  f32x16 zero;
+#pragma unroll
+  for (int j = 0; j < 16; ++j) zero[j] = 0.f;
+#pragma unroll
+  for (int ks = 0; ks < AHEAD; ++ks) {
+    x0[ks] = lds_read_b128(Xs, a_base + ks * 32);
+    x1[ks] = lds_read_b128(Xs, a_base + 32 * kRowBytes + ks * 32);
+  }
+  DFA_SCHED_FENCE();
+#pragma unroll
+  for (int ks = 0; ks < 8; ++ks) {
+    if (ks + AHEAD < 8) {
+      x0[(ks + AHEAD) % (AHEAD + 1)] = lds_read_b128(Xs, a_base + (ks + AHEAD) * 32);
+      x1[(ks + AHEAD) % (AHEAD + 1)] = lds_read_b128(Xs, a_base + 32 * kRowBytes + (ks + AHEAD) * 32);
+    }
+    c0 = mfma32(x0[ks % (AHEAD + 1)], bT[ks], ks == 0 ? zero : c0);
+    c1 = mfma32(x1[ks % (AHEAD + 1)], bT[ks], ks == 0 ? zero : c1);
+    DFA_SCHED_FENCE();
+  }
+}
+
+// acc[db] += Y^T[db block of d][64 queries] * W[64 queries][32 keys]: Y^T is gathered from the
+// row-major LDS tile with the transposing read, W (P or dS) comes from registers in the order
+// an MFMA result tile has (w[qb][half] = rows (e/4)*8 + 4h + e%4 of 16-row half `half`).
+__device__ __forceinline__ void col_products(f32x16 (&acc)[4], const char* Ys, int g_base,
+                                             const bf16x8 (&w)[2][2]) {
+  constexpr int AHEAD = 4;
+  bf16x8 y[AHEAD + 1];
+  auto off = [&](int n) {                 // n = qb * 8 + half * 4 + db
+    return g_base + ((n >> 3) * 32 + ((n >> 2) & 1) * 16) * kRowBytes + (n & 3) * 64;
+  };
+#pragma unroll
+  for (int n = 0; n < AHEAD; ++n) y[n] = lds_gather(Ys, off(n));
+  DFA_SCHED_FENCE();
+#pragma unroll
+  for (int n = 0; n < 16; ++n) {
+    if (n + AHEAD < 16) y[(n + AHEAD) % (AHEAD + 1)] = lds_gather(Ys, off(n + AHEAD));
+    acc[n & 3] = mfma32(y[n % (AHEAD + 1)], w[n >> 3][(n >> 2) & 1], acc[n & 3]);
+    DFA_SCHED_FENCE();
+  }
+}
+
+__global__ void __launch_bounds__(NT, 2) k_bwd_dkdv_bf16(BwdParams p) {
   extern __shared__ __align__(16) char smem[];
-  // Buffer b: Q at b*BUF, dO at b*BUF + QTILE, lse'[64] and D[64] at b*BUF + 2*QTILE.
 
   // XCD-aware mapping: workgroup ids go round-robin over the 8 XCDs; give every XCD a contiguous
   // range of (kv head, key tile) items so that the tiles of one head share Q/dO in one L2.
@@ -111,181 +168,169 @@ __global__ void __launch_bounds__(NTHREADS, 1) k_bwd_dkdv_bf16(BwdParams p) {
   const int k0 = tk * BN;
 
   const int tid = threadIdx.x, lane = tid & 63;
-  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform: keeps tile branches scalar
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform: role branches stay scalar
+  const int kb = wave & 3;            // 32-key block of this wavefront
+  const bool dp_wave = wave >= 4;     // false: S, P, dV;  true: dP, dS, dK
   const int r32 = lane & 31, hh = lane >> 5;
-  const int kvrow = k0 + wave * 32 + r32;
+  const int kvrow = k0 + kb * 32 + r32;
   const bool kvalid = kvrow < p.s_k;
   // per-lane LDS bases; everything else in an LDS address is a compile-time constant
   const int a_base = tile_off(r32, hh);                       // row reads (A operand of S, dP)
   const int g_base = gather_base(lane);                       // transposed gathers of Q, dO
 
-  // K^T and V^T B operands of this wavefront's 32 keys (contraction over d)
-  bf16x8 kT[8], vT[8];
+  // B operands over d of this wavefront's 32 keys: K^T for an S wavefront, V^T for a dP wavefront
+  bf16x8 bT[8];
   {
+    const __bf16* src = dp_wave ? p.v : p.k;
     const int64_t off = kh * p.kv_sh + static_cast<int64_t>(kvalid ? kvrow : 0) * p.kv_ss + 8 * hh;
 #pragma unroll
     for (int ks = 0; ks < 8; ++ks) {
-      uint4 a = *reinterpret_cast<const uint4*>(p.k + off + 16 * ks);
-      uint4 b = *reinterpret_cast<const uint4*>(p.v + off + 16 * ks);
-      if (!kvalid) { a = make_uint4(0, 0, 0, 0); b = make_uint4(0, 0, 0, 0); }
-      kT[ks] = __builtin_bit_cast(bf16x8, a);
-      vT[ks] = __builtin_bit_cast(bf16x8, b);
+      uint4 a = *reinterpret_cast<const uint4*>(src + off + 16 * ks);
+      if (!kvalid) a = make_uint4(0, 0, 0, 0);
+      bT[ks] = __builtin_bit_cast(bf16x8, a);
     }
   }
 
-  f32x16 dvT[4], dkT[4];
+  // dV^T (S wavefront) or dK^T (dP wavefront): [d block][d within block][key]
+  f32x16 acc[4];
 #pragma unroll
   for (int i = 0; i < 4; ++i)
 #pragma unroll
-    for (int j = 0; j < 16; ++j) { dvT[i][j] = 0.f; dkT[i][j] = 0.f; }
+    for (int j = 0; j < 16; ++j) acc[i][j] = 0.f;
 
   const float c2 = p.scale * LOG2E;
   const int q_begin = p.causal ? k0 : 0;            // k0 is a multiple of BM
   const int ntq = (p.s_q - q_begin + BM - 1) / BM;  // query tiles per head for this key tile
   const int niter = ntq * p.group;
-  const bool k_edge = k0 + BN > p.s_k;
 
   QTileRegs tr;
   if (niter > 0) {
     qtile_load<true>(tr, p, kh * p.group, q_begin, tid);
-    qtile_store(tr, smem, smem + QTILE_BYTES, reinterpret_cast<float*>(smem + 2 * QTILE_BYTES), tid);
+    qtile_store(tr, smem + OFF_Q, smem + OFF_G, reinterpret_cast<float*>(smem + OFF_LD), tid);
   }
   __syncthreads();
 
-  for (int it = 0; it < niter; ++it) {
-    const int q0 = q_begin + (it % ntq) * BM;
-    const bool more = it + 1 < niter;
-    const int boff = (it & 1) * BUF_BYTES;
-    const char* Qs = smem + boff;
-    const char* Gs = Qs + QTILE_BYTES;
-    const float* LDs = reinterpret_cast<const float*>(Qs + 2 * QTILE_BYTES);
-    char* Qn = smem + (BUF_BYTES - boff);              // buffer of the next tile
-    const bool edge = k_edge || (q0 + BM > p.s_q) || (p.causal && q0 < k0 + BN - 1);
+  // One barrier per tile.  Between two barriers ("slot" t) the S wavefronts take tile t all the
+  // way (S, P, hand P over through LDS, dV) while the dP wavefronts finish tile t-1 (dS, dK) and
+  // then start tile t (dP).  The two kinds share each SIMD, so the exponentials of one overlap
+  // the MFMAs of the other.  Both kinds run niter + 1 slots (the S wavefronts idle in the last,
+  // the dP wavefronts have no dS/dK in the first); each kind has its own straight-line loop.
+  int slot = 0;            // t % 3
+  auto prefetch = [&](int it) {        // global loads of tile it + 1 (all 512 threads)
+    const int hq_n = kh * p.group + (it + 1) / ntq;
+    const int q0_n = q_begin + ((it + 1) % ntq) * BM;
+    if (q0_n + BM <= p.s_q) qtile_load<false>(tr, p, hq_n, q0_n, tid);
+    else qtile_load<true>(tr, p, hq_n, q0_n, tid);
+  };
+  auto commit = [&](int it, int next) {
+    qtile_store(tr, smem + OFF_Q + next * QTILE_BYTES, smem + OFF_G + ((it + 1) & 1) * QTILE_BYTES,
+                reinterpret_cast<float*>(smem + OFF_LD + next * LD_BYTES), tid);
+  };
 
-    // The tile is two blocks of 32 queries, software-pipelined by hand inside the wavefront (one
-    // wavefront per SIMD here, so nothing else hides latencies): the MFMAs of one block are
-    // issued between slices of the exp/VALU work of the other, and every LDS operand is read
-    // 2-4 MFMA steps before it is used.  DFA_SCHED_FENCE pins that order.
-#define DFA_RA(QB, KS, SL)                                                         \
-  {                                                                                \
-    const int off_ = a_base + (QB) * 32 * kRowBytes + (KS) * 32;                   \
-    qa[SL] = lds_read_b128(Qs, off_);                                              \
-    ga[SL] = lds_read_b128(Gs, off_);                                              \
-  }
-#define DFA_RG(QB, I, SL)                                                          \
-  {                                                                                \
-    const int off_ = g_base + ((QB) * 32 + ((I) >> 2) * 16) * kRowBytes + ((I) & 3) * 64; \
-    gd[SL] = lds_gather(Gs, off_);                                                 \
-    gq[SL] = lds_gather(Qs, off_);                                                 \
-  }
-#define DFA_RLD(QB, G4, SL)                                                        \
-  {                                                                                \
-    L4[SL] = *reinterpret_cast<const f32x4*>(LDs + (QB) * 32 + (G4) * 8 + hh * 4); \
-    D4[SL] = *reinterpret_cast<const f32x4*>(LDs + 64 + (QB) * 32 + (G4) * 8 + hh * 4); \
-  }
-#define DFA_BELEM(S, DP, QB, J)                                                    \
-  {                                                                                \
-    float pr_ = __builtin_amdgcn_exp2f(fmaf(S[J], c2, -L4[((J) >> 2) & 1][(J) & 3])); \
-    if (edge) {                                                                    \
-      const int qrow_ = q0 + (QB) * 32 + ((J) >> 2) * 8 + hh * 4 + ((J) & 3);       \
-      pr_ = (!kvalid || (p.causal && kvrow > qrow_)) ? 0.f : pr_;                  \
-    }                                                                              \
-    S[J] = pr_;                                                                    \
-    DP[J] = pr_ * (DP[J] - D4[((J) >> 2) & 1][(J) & 3]);                           \
-  }
-    {
-      bf16x8 qa[4], ga[4], gd[2], gq[2], pb0[2], sb0[2], pb1[2], sb1[2];
-      f32x4 L4[2], D4[2];
-      f32x16 s0, dp0, s1, dp1;
+  if (!dp_wave) {
+    for (int it = 0; it < niter; ++it) {
+      const bool more = it + 1 < niter;
+      const int next = slot == 2 ? 0 : slot + 1;
+      const char* Qs = smem + OFF_Q + slot * QTILE_BYTES;
+      const char* Gs = smem + OFF_G + (it & 1) * QTILE_BYTES;
+      const float* Ls = reinterpret_cast<const float*>(smem + OFF_LD + slot * LD_BYTES);
+      const int q0 = q_begin + (it % ntq) * BM;
+      if (more) prefetch(it);
+      f32x16 c0, c1;
+      row_products(c0, c1, Qs, a_base, bT);          // S = Q K^T
+      // Only the causal diagonal needs a mask: query rows past s_q carry lse' = +inf (P = 0)
+      // and key rows past s_k only feed dk/dv rows that are never written.
+      if (p.causal && q0 < k0 + BN - 1) {
 #pragma unroll
-      for (int j = 0; j < 16; ++j) { s0[j] = 0.f; dp0[j] = 0.f; s1[j] = 0.f; dp1[j] = 0.f; }
-#pragma unroll
-      for (int ks = 0; ks < 4; ++ks) DFA_RA(0, ks, ks)
-      DFA_RLD(0, 0, 0)
-      if (more) {   // global loads of the next tile; stored to the other LDS buffer after the tile
-        const int hq_n = kh * p.group + (it + 1) / ntq;
-        const int q0_n = q_begin + ((it + 1) % ntq) * BM;
-        if (q0_n + BM <= p.s_q) qtile_load<false>(tr, p, hq_n, q0_n, tid);
-        else qtile_load<true>(tr, p, hq_n, q0_n, tid);
+        for (int j = 0; j < 16; ++j) {
+          const int qrow = q0 + (j >> 2) * 8 + hh * 4 + (j & 3);
+          c0[j] = kvrow > qrow ? -INFINITY : c0[j];
+          c1[j] = kvrow > qrow + 32 ? -INFINITY : c1[j];
+        }
       }
-      DFA_SCHED_FENCE();
-      // stage 1: S, dP of block 0
 #pragma unroll
-      for (int ks = 0; ks < 8; ++ks) {
-        s0 = mfma32(qa[ks & 3], kT[ks], s0);
-        dp0 = mfma32(ga[ks & 3], vT[ks], dp0);
-        if (ks < 4) DFA_RA(0, ks + 4, ks & 3) else DFA_RA(1, ks - 4, ks & 3)
-        DFA_SCHED_FENCE();
-      }
-      // stage 2: S, dP of block 1 between slices of P, dS of block 0
+      for (int g4 = 0; g4 < 4; ++g4) {
+        const f32x4 l0 = *reinterpret_cast<const f32x4*>(Ls + g4 * 8 + hh * 4);
+        const f32x4 l1 = *reinterpret_cast<const f32x4*>(Ls + 32 + g4 * 8 + hh * 4);
 #pragma unroll
-      for (int ks = 0; ks < 8; ++ks) {
-        s1 = mfma32(qa[ks & 3], kT[ks], s1);
-        dp1 = mfma32(ga[ks & 3], vT[ks], dp1);
-        if (ks < 4) DFA_RA(1, ks + 4, ks & 3)
-        if (ks == 4) DFA_RG(0, 0, 0)
-        if (ks == 5) DFA_RG(0, 1, 1)
-        if ((ks & 1) == 0 && ks < 6) DFA_RLD(0, ks / 2 + 1, (ks / 2 + 1) & 1)
-        if (ks == 6) DFA_RLD(1, 0, 0)
-        DFA_BELEM(s0, dp0, 0, 2 * ks)
-        DFA_BELEM(s0, dp0, 0, 2 * ks + 1)
-        if (ks == 4) pb0[0] = pack8(s0, 0);
-        if (ks == 5) sb0[0] = pack8(dp0, 0);
-        DFA_SCHED_FENCE();
+        for (int e = 0; e < 4; ++e) {
+          c0[g4 * 4 + e] = __builtin_amdgcn_exp2f(fmaf(c0[g4 * 4 + e], c2, -l0[e]));
+          c1[g4 * 4 + e] = __builtin_amdgcn_exp2f(fmaf(c1[g4 * 4 + e], c2, -l1[e]));
+        }
       }
-      // stage 3: dV^T, dK^T of block 0 between slices of P, dS of block 1
+      bf16x8 w[2][2];
+      w[0][0] = pack8(c0, 0); w[0][1] = pack8(c0, 8);
+      w[1][0] = pack8(c1, 0); w[1][1] = pack8(c1, 8);
+      {  // hand P to the dP wavefront of the same key block: lane-private, any layout will do
+        char* px = smem + OFF_PX + (it & 1) * PX_BYTES + kb * 4096 + lane * 16;
 #pragma unroll
-      for (int i = 0; i < 8; ++i) {
-        if (i == 0) pb0[1] = pack8(s0, 8);       // first used at i == 4
-        if (i == 1) sb0[1] = pack8(dp0, 8);
-        dvT[i & 3] = mfma32(gd[i & 1], pb0[i >> 2], dvT[i & 3]);
-        dkT[i & 3] = mfma32(gq[i & 1], sb0[i >> 2], dkT[i & 3]);
-        if (i + 2 < 8) DFA_RG(0, i + 2, i & 1) else DFA_RG(1, i - 6, i & 1)
-        if ((i & 1) == 0 && i < 6) DFA_RLD(1, i / 2 + 1, (i / 2 + 1) & 1)
-        DFA_BELEM(s1, dp1, 1, 2 * i)
-        DFA_BELEM(s1, dp1, 1, 2 * i + 1)
-        if (i == 4) pb1[0] = pack8(s1, 0);
-        if (i == 5) sb1[0] = pack8(dp1, 0);
-        DFA_SCHED_FENCE();
+        for (int j = 0; j < 4; ++j) *reinterpret_cast<bf16x8*>(px + j * 1024) = w[j >> 1][j & 1];
       }
-      // stage 4: dV^T, dK^T of block 1
-#pragma unroll
-      for (int i = 0; i < 8; ++i) {
-        if (i == 0) pb1[1] = pack8(s1, 8);
-        if (i == 1) sb1[1] = pack8(dp1, 8);
-        dvT[i & 3] = mfma32(gd[i & 1], pb1[i >> 2], dvT[i & 3]);
-        dkT[i & 3] = mfma32(gq[i & 1], sb1[i >> 2], dkT[i & 3]);
-        if (i + 2 < 8) DFA_RG(1, i + 2, i & 1)
-        DFA_SCHED_FENCE();
-      }
+      col_products(acc, Gs, g_base, w);              // dV^T += dO^T P
+      if (more) commit(it, next);
+      __syncthreads();
+      slot = next;
     }
-#undef DFA_RA
-#undef DFA_RG
-#undef DFA_RLD
-#undef DFA_BELEM
-    if (more) qtile_store(tr, Qn, Qn + QTILE_BYTES, reinterpret_cast<float*>(Qn + 2 * QTILE_BYTES), tid);
+    __syncthreads();      // the dP wavefronts' last slot
+  } else {
+    f32x16 c0, c1;        // dP of the tile in flight, carried over the barrier
+    auto finish_prev = [&](int it, int prev) {       // dS and dK of tile it - 1
+      const float* Ds = reinterpret_cast<const float*>(smem + OFF_LD + prev * LD_BYTES) + 64;
+      const char* px = smem + OFF_PX + ((it & 1) ^ 1) * PX_BYTES + kb * 4096 + lane * 16;
+      bf16x8 w[2][2];
+#pragma unroll
+      for (int j = 0; j < 4; ++j) w[j >> 1][j & 1] = *reinterpret_cast<const bf16x8*>(px + j * 1024);
+#pragma unroll
+      for (int g4 = 0; g4 < 4; ++g4) {
+        const f32x4 d0 = *reinterpret_cast<const f32x4*>(Ds + g4 * 8 + hh * 4);
+        const f32x4 d1 = *reinterpret_cast<const f32x4*>(Ds + 32 + g4 * 8 + hh * 4);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          const int j = g4 * 4 + e;
+          c0[j] = static_cast<float>(w[0][j >> 3][j & 7]) * (c0[j] - d0[e]);
+          c1[j] = static_cast<float>(w[1][j >> 3][j & 7]) * (c1[j] - d1[e]);
+        }
+      }
+      w[0][0] = pack8(c0, 0); w[0][1] = pack8(c0, 8);
+      w[1][0] = pack8(c1, 0); w[1][1] = pack8(c1, 8);
+      col_products(acc, smem + OFF_Q + prev * QTILE_BYTES, g_base, w);   // dK^T += Q^T dS
+    };
+    {  // slot 0: dP of tile 0 only
+      if (niter > 1) prefetch(0);
+      row_products(c0, c1, smem + OFF_G, a_base, bT);
+      if (niter > 1) commit(0, 1);
+      __syncthreads();
+      slot = 1;
+    }
+    for (int it = 1; it < niter; ++it) {
+      const bool more = it + 1 < niter;
+      const int prev = slot == 0 ? 2 : slot - 1, next = slot == 2 ? 0 : slot + 1;
+      if (more) prefetch(it);
+      finish_prev(it, prev);
+      row_products(c0, c1, smem + OFF_G + (it & 1) * QTILE_BYTES, a_base, bT);   // dP = dO V^T
+      if (more) commit(it, next);
+      __syncthreads();
+      slot = next;
+    }
+    finish_prev(niter, slot == 0 ? 2 : slot - 1);
     __syncthreads();
   }
 
   if (kvalid) {
-    float* dkp = p.dk + kh * p.dkv_sh + static_cast<int64_t>(kvrow) * p.dkv_ss;
-    float* dvp = p.dv + kh * p.dkv_sh + static_cast<int64_t>(kvrow) * p.dkv_ss;
+    float* dst = (dp_wave ? p.dk : p.dv) + kh * p.dkv_sh + static_cast<int64_t>(kvrow) * p.dkv_ss;
+    const float f = dp_wave ? p.scale : 1.f;
 #pragma unroll
     for (int db = 0; db < 4; ++db)
 #pragma unroll
       for (int g4 = 0; g4 < 4; ++g4) {
         const int col = db * 32 + g4 * 8 + hh * 4;
-        float4 a = make_float4(dkT[db][g4 * 4] * p.scale, dkT[db][g4 * 4 + 1] * p.scale,
-                               dkT[db][g4 * 4 + 2] * p.scale, dkT[db][g4 * 4 + 3] * p.scale);
-        float4 b = make_float4(dvT[db][g4 * 4], dvT[db][g4 * 4 + 1], dvT[db][g4 * 4 + 2], dvT[db][g4 * 4 + 3]);
+        float4 a = make_float4(acc[db][g4 * 4] * f, acc[db][g4 * 4 + 1] * f, acc[db][g4 * 4 + 2] * f,
+                               acc[db][g4 * 4 + 3] * f);
         if (p.accumulate) {
-          const float4 a0 = *reinterpret_cast<const float4*>(dkp + col);
-          const float4 b0 = *reinterpret_cast<const float4*>(dvp + col);
+          const float4 a0 = *reinterpret_cast<const float4*>(dst + col);
           a.x += a0.x; a.y += a0.y; a.z += a0.z; a.w += a0.w;
-          b.x += b0.x; b.y += b0.y; b.z += b0.z; b.w += b0.w;
         }
-        *reinterpret_cast<float4*>(dkp + col) = a;
-        *reinterpret_cast<float4*>(dvp + col) = b;
+        *reinterpret_cast<float4*>(dst + col) = a;
       }
   }
 }
@@ -499,7 +544,7 @@ int launch_bwd_bf16(const dfa_shape& sh, const void* q, const void* k, const voi
     if (total > (1 << 30)) return DFA_ERR_SHAPE;
     a.total = static_cast<int>(total);
     a.per_xcd = (a.total + 7) / 8;
-    const size_t smem = 2 * kv::BUF_BYTES;
+    const size_t smem = kv::SMEM_BYTES;
     static bool attr_set = false;   // > 64 KB of dynamic LDS needs the opt-in once per process
     if (!attr_set) {
       const int rc = hip_status(hipFuncSetAttribute(reinterpret_cast<const void*>(kv::k_bwd_dkdv_bf16),
@@ -508,7 +553,7 @@ int launch_bwd_bf16(const dfa_shape& sh, const void* q, const void* k, const voi
       if (rc) return rc;
       attr_set = true;
     }
-    kv::k_bwd_dkdv_bf16<<<a.per_xcd * 8, NTHREADS, smem, st>>>(a);
+    kv::k_bwd_dkdv_bf16<<<a.per_xcd * 8, kv::NT, smem, st>>>(a);
     const int rc = last_launch_status();
     if (rc) return rc;
   }
