@@ -25,7 +25,8 @@ int check_common(const dfa_shape* sh) {
 bool stride_ok(int64_t sh_, int64_t ss, int d, int rows) {
   if (ss < d || !mult8(ss) || !mult8(sh_)) return false;
   if (sh_ < 0) return false;
-  (void)rows;
+  // the kernels address one head's slice of a chunk with 32-bit byte offsets (fp32 at most)
+  if (static_cast<int64_t>(rows) * ss * 4 >= (int64_t{1} << 31)) return false;
   return true;
 }
 

@@ -60,51 +60,74 @@ constexpr int OFF_LD = OFF_G + 2 * QTILE_BYTES;
 constexpr int OFF_PX = OFF_LD + 3 * LD_BYTES;
 constexpr int SMEM_BYTES = OFF_PX + 2 * PX_BYTES;
 
-struct QTileRegs { uint4 q[2], g[2]; float ld; };
+// The Q and dO tiles go from global memory straight into LDS (global_load_lds_dwordx4: every
+// lane supplies its own global address, the wavefront's 64 x 16 bytes land contiguously at the
+// LDS address in M0).  A padded tile is 17 such 1 KB pieces; S wavefront w moves pieces w, w + 4,
+// w + 8, w + 12 and (w = 0 only) 16.  Byte 16 s of the tile is chunk s % 17 of physical row
+// s / 17; chunk 16 is the pad (it receives a copy of chunk 15).  Only lse / D pass through a
+// register.  The dP wavefronts move nothing: the compiler makes a wavefront wait for its own
+// outstanding copies before its next transposing LDS read, which for them comes at once.
+struct QTileRegs { float ld; bool ld_ok; };
 
-template <bool EDGE>
-__device__ __forceinline__ void qtile_load(QTileRegs& t, const BwdParams& p, int hq, int q0, int tid) {
-  const int c = tid & 15;
-  const __bf16* qg = p.q + hq * p.q_sh;
-  const __bf16* gg = p.dO + hq * p.q_sh;
+struct QTileLane { int row[5]; uint32_t cb[5]; };   // this lane's logical tile row and byte in the row, per piece
+
+__device__ __forceinline__ QTileLane qtile_lane(int wave, int lane) {
+  QTileLane m;
 #pragma unroll
-  for (int i = 0; i < 2; ++i) {
-    const int r = (tid >> 4) + 32 * i;
-    if (!EDGE || q0 + r < p.s_q) {
-      const int64_t off = static_cast<int64_t>(q0 + r) * p.q_ss + c * 8;
-      t.q[i] = *reinterpret_cast<const uint4*>(qg + off);
-      t.g[i] = *reinterpret_cast<const uint4*>(gg + off);
-    } else {
-      t.q[i] = make_uint4(0, 0, 0, 0);
-      t.g[i] = make_uint4(0, 0, 0, 0);
-    }
+  for (int j = 0; j < 5; ++j) {
+    const int s = (wave + 4 * j) * 64 + lane;
+    m.row[j] = prow(s / 17);                       // prow is its own inverse
+    m.cb[j] = static_cast<uint32_t>(min(s % 17, 15)) * 16;
   }
-  // threads 0..63 fetch lse (pre-multiplied by log2 e), threads 64..127 fetch D
-  t.ld = 0.f;
-  if (tid < 128) {
-    const int r = tid & 63;
-    const bool ok = !EDGE || q0 + r < p.s_q;
-    const int idx = ok ? q0 + r : 0;
-    if (tid < 64) {
-      const float L = p.lse[hq * p.l_sh + idx];
-      t.ld = (ok && L > -INFINITY) ? L * LOG2E : INFINITY;   // +inf makes P exactly 0 for that row
-    } else {
-      const float dl = p.delta[hq * p.l_sh + idx];
-      t.ld = ok ? dl : 0.f;
-    }
+  return m;
+}
+
+// Where the next (Q, dO, lse, D) tile comes from: wave-uniform head bases, advanced tile by
+// tile (no division in the loop), plus per-thread 32-bit byte offsets inside the head.
+struct QTileCursor {
+  const char *qh, *gh;       // Q and dO of the head
+  const float* ldh;          // lse (even wavefronts) or D (odd wavefronts) of the head
+  int q0;                    // first query row of the tile
+};
+
+// Cursor to the next tile: the next rows, or the next query head of the group.
+__device__ __forceinline__ void qtile_advance(QTileCursor& cur, const BwdParams& p, int q_begin, int q_end) {
+  cur.q0 += 64;
+  if (cur.q0 >= q_end) {
+    cur.q0 = q_begin;
+    cur.qh += p.q_sh * 2; cur.gh += p.q_sh * 2; cur.ldh += p.l_sh;
   }
 }
 
-__device__ __forceinline__ void qtile_store(const QTileRegs& t, char* Qs, char* Gs, float* LDs, int tid) {
-  const int c = tid & 15;
+__device__ __forceinline__ void dma16(const char* g, char* lds_uniform) {
+  __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)g,
+                                   (DFA_LDS void*)lds_uniform, 16, 0, 0);
+}
+
+// Rows past s_q are clamped to the last row instead of zero-filled: their lse' is +inf, so P and
+// dS vanish for them whatever (finite) Q and dO the tile holds.  Qs, Gs: LDS tiles to fill.
+__device__ __forceinline__ void qtile_load(QTileRegs& t, const QTileCursor& cur, const QTileLane& m,
+                                           const BwdParams& p, char* Qs, char* Gs, int wave, int tid) {
+  const uint32_t rowbytes = static_cast<uint32_t>(p.q_ss) * 2;
+  const int last = p.s_q - 1;
 #pragma unroll
-  for (int i = 0; i < 2; ++i) {
-    const int r = (tid >> 4) + 32 * i;
-    const int off = tile_off(r, c);
-    *reinterpret_cast<uint4*>(Qs + off) = t.q[i];
-    *reinterpret_cast<uint4*>(Gs + off) = t.g[i];
+  for (int j = 0; j < 5; ++j) {
+    if (j < 4 || wave == 0) {
+      const uint32_t off = static_cast<uint32_t>(min(cur.q0 + m.row[j], last)) * rowbytes + m.cb[j];
+      dma16(cur.qh + off, Qs + (wave + 4 * j) * 1024);
+      dma16(cur.gh + off, Gs + (wave + 4 * j) * 1024);
+    }
   }
-  if (tid < 128) LDs[tid] = t.ld;
+  const int r = cur.q0 + (tid & 63);
+  t.ld_ok = r <= last;
+  t.ld = cur.ldh[static_cast<uint32_t>(min(r, last))];
+}
+
+__device__ __forceinline__ void qtile_store(const QTileRegs& t, float* LDs, int tid) {
+  if (tid < 64)   // lse pre-multiplied by log2 e; +inf makes P exactly 0 for an absent or empty row
+    LDs[tid] = (t.ld_ok && t.ld > -INFINITY) ? t.ld * LOG2E : INFINITY;
+  else if (tid < 128)
+    LDs[tid] = t.ld_ok ? t.ld : 0.f;
 }
 
 // C[qb] = X[qb rows] * B^T over d for both 32-row blocks of the tile: X rows are read from LDS
@@ -204,9 +227,20 @@ __global__ void __launch_bounds__(NT, 2) k_bwd_dkdv_bf16(BwdParams p) {
   const int niter = ntq * p.group;
 
   QTileRegs tr;
-  if (niter > 0) {
-    qtile_load<true>(tr, p, kh * p.group, q_begin, tid);
-    qtile_store(tr, smem + OFF_Q, smem + OFF_G, reinterpret_cast<float*>(smem + OFF_LD), tid);
+  QTileCursor cur;
+  {
+    const int hq0 = kh * p.group;
+    cur.qh = reinterpret_cast<const char*>(p.q + hq0 * p.q_sh);
+    cur.gh = reinterpret_cast<const char*>(p.dO + hq0 * p.q_sh);
+    cur.ldh = ((wave & 1) ? p.delta : p.lse) + hq0 * p.l_sh;
+    cur.q0 = q_begin;
+  }
+  const int q_end = q_begin + ntq * BM;
+  const QTileLane tl = qtile_lane(kb, lane);
+  if (!dp_wave) {
+    qtile_load(tr, cur, tl, p, smem + OFF_Q, smem + OFF_G, wave, tid);
+    qtile_store(tr, reinterpret_cast<float*>(smem + OFF_LD), tid);
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");     // this wavefront's copies into LDS have landed
   }
   __syncthreads();
 
@@ -216,16 +250,16 @@ __global__ void __launch_bounds__(NT, 2) k_bwd_dkdv_bf16(BwdParams p) {
   // the MFMAs of the other.  Both kinds run niter + 1 slots (the S wavefronts idle in the last,
   // the dP wavefronts have no dS/dK in the first); each kind has its own straight-line loop.
   int slot = 0;            // t % 3
-  auto prefetch = [&](int it) {        // global loads of tile it + 1 (all 512 threads)
-    const int hq_n = kh * p.group + (it + 1) / ntq;
-    const int q0_n = q_begin + ((it + 1) % ntq) * BM;
-    if (q0_n + BM <= p.s_q) qtile_load<false>(tr, p, hq_n, q0_n, tid);
-    else qtile_load<true>(tr, p, hq_n, q0_n, tid);
-  };
-  auto commit = [&](int it, int next) {
-    qtile_store(tr, smem + OFF_Q + next * QTILE_BYTES, smem + OFF_G + ((it + 1) & 1) * QTILE_BYTES,
-                reinterpret_cast<float*>(smem + OFF_LD + next * LD_BYTES), tid);
-  };
+  // DFA_PREFETCH(IT, NEXT): start moving tile IT + 1 into its ring slots; DFA_COMMIT: lse / D.
+  // The copies into LDS are complete at the barrier that ends the slot (the barrier's release
+  // fence waits for them).
+#define DFA_PREFETCH(IT, NEXT)                                                                   \
+  {                                                                                              \
+    qtile_advance(cur, p, q_begin, q_end);                                                       \
+    qtile_load(tr, cur, tl, p, smem + OFF_Q + (NEXT) * QTILE_BYTES,                              \
+               smem + OFF_G + (((IT) + 1) & 1) * QTILE_BYTES, wave, tid);                        \
+  }
+#define DFA_COMMIT(NEXT) qtile_store(tr, reinterpret_cast<float*>(smem + OFF_LD + (NEXT) * LD_BYTES), tid);
 
   if (!dp_wave) {
     for (int it = 0; it < niter; ++it) {
@@ -235,7 +269,7 @@ __global__ void __launch_bounds__(NT, 2) k_bwd_dkdv_bf16(BwdParams p) {
       const char* Gs = smem + OFF_G + (it & 1) * QTILE_BYTES;
       const float* Ls = reinterpret_cast<const float*>(smem + OFF_LD + slot * LD_BYTES);
       const int q0 = q_begin + (it % ntq) * BM;
-      if (more) prefetch(it);
+      if (more) DFA_PREFETCH(it, next)
       f32x16 c0, c1;
       row_products(c0, c1, Qs, a_base, bT);          // S = Q K^T
       // Only the causal diagonal needs a mask: query rows past s_q carry lse' = +inf (P = 0)
@@ -267,17 +301,18 @@ __global__ void __launch_bounds__(NT, 2) k_bwd_dkdv_bf16(BwdParams p) {
         for (int j = 0; j < 4; ++j) *reinterpret_cast<bf16x8*>(px + j * 1024) = w[j >> 1][j & 1];
       }
       col_products(acc, Gs, g_base, w);              // dV^T += dO^T P
-      if (more) commit(it, next);
+      if (more) DFA_COMMIT(next)
+      asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // this wavefront's copies into LDS have landed
       __syncthreads();
       slot = next;
     }
     __syncthreads();      // the dP wavefronts' last slot
   } else {
     f32x16 c0, c1;        // dP of the tile in flight, carried over the barrier
-    auto finish_prev = [&](int it, int prev) {       // dS and dK of tile it - 1
+    bf16x8 w[2][2];
+    auto dS_prev = [&](int it, int prev) {           // dS of tile it - 1 from P (LDS) and dP (registers)
       const float* Ds = reinterpret_cast<const float*>(smem + OFF_LD + prev * LD_BYTES) + 64;
       const char* px = smem + OFF_PX + ((it & 1) ^ 1) * PX_BYTES + kb * 4096 + lane * 16;
-      bf16x8 w[2][2];
 #pragma unroll
       for (int j = 0; j < 4; ++j) w[j >> 1][j & 1] = *reinterpret_cast<const bf16x8*>(px + j * 1024);
 #pragma unroll
@@ -293,28 +328,27 @@ __global__ void __launch_bounds__(NT, 2) k_bwd_dkdv_bf16(BwdParams p) {
       }
       w[0][0] = pack8(c0, 0); w[0][1] = pack8(c0, 8);
       w[1][0] = pack8(c1, 0); w[1][1] = pack8(c1, 8);
-      col_products(acc, smem + OFF_Q + prev * QTILE_BYTES, g_base, w);   // dK^T += Q^T dS
     };
     {  // slot 0: dP of tile 0 only
-      if (niter > 1) prefetch(0);
       row_products(c0, c1, smem + OFF_G, a_base, bT);
-      if (niter > 1) commit(0, 1);
       __syncthreads();
       slot = 1;
     }
     for (int it = 1; it < niter; ++it) {
-      const bool more = it + 1 < niter;
       const int prev = slot == 0 ? 2 : slot - 1, next = slot == 2 ? 0 : slot + 1;
-      if (more) prefetch(it);
-      finish_prev(it, prev);
+      dS_prev(it, prev);
+      col_products(acc, smem + OFF_Q + prev * QTILE_BYTES, g_base, w);           // dK^T += Q^T dS
       row_products(c0, c1, smem + OFF_G + (it & 1) * QTILE_BYTES, a_base, bT);   // dP = dO V^T
-      if (more) commit(it, next);
       __syncthreads();
       slot = next;
     }
-    finish_prev(niter, slot == 0 ? 2 : slot - 1);
+    dS_prev(niter, slot == 0 ? 2 : slot - 1);
+    col_products(acc, smem + OFF_Q + (slot == 0 ? 2 : slot - 1) * QTILE_BYTES, g_base, w);
     __syncthreads();
   }
+
+#undef DFA_PREFETCH
+#undef DFA_COMMIT
 
   if (kvalid) {
     float* dst = (dp_wave ? p.dk : p.dv) + kh * p.dkv_sh + static_cast<int64_t>(kvrow) * p.dkv_ss;
