@@ -380,40 +380,8 @@ constexpr int BM = 128;     // query rows per workgroup
 constexpr int BN = 64;      // key rows per LDS tile
 constexpr int TILE_BYTES = BN * kRowBytes;
 
-struct TileRegs { uint4 k[4], v[4]; };
-
-__device__ __forceinline__ void tile_load(TileRegs& t, const __bf16* kg, const __bf16* vg, int64_t ss,
-                                          int k0, int s_k, int tid) {
-  const int c = tid & 15;
-#pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    const int r = (tid >> 4) + 16 * i;
-    if (k0 + r < s_k) {
-      const int64_t off = static_cast<int64_t>(k0 + r) * ss + c * 8;
-      t.k[i] = *reinterpret_cast<const uint4*>(kg + off);
-      t.v[i] = *reinterpret_cast<const uint4*>(vg + off);
-    } else {
-      t.k[i] = make_uint4(0, 0, 0, 0);
-      t.v[i] = make_uint4(0, 0, 0, 0);
-    }
-  }
-}
-
-__device__ __forceinline__ void tile_store(const TileRegs& t, char* Ks, char* Vs, int tid) {
-  const int c = tid & 15;
-#pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    const int r = (tid >> 4) + 16 * i;
-    const int off = tile_off(r, c);
-    *reinterpret_cast<uint4*>(Ks + off) = t.k[i];
-    *reinterpret_cast<uint4*>(Vs + off) = t.v[i];
-  }
-}
-
 __global__ void __launch_bounds__(NTHREADS, 2) k_bwd_dq_bf16(BwdParams p) {
-  extern __shared__ __align__(16) char smem[];
-  char* Ks = smem;
-  char* Vs = smem + TILE_BYTES;
+  extern __shared__ __align__(16) char smem[];   // two (K tile, V tile) buffers
 
   const int bid = blockIdx.x;
   const int item = (bid & 7) * p.per_xcd + (bid >> 3);   // contiguous (head, query tile) range per XCD
@@ -433,8 +401,10 @@ __global__ void __launch_bounds__(NTHREADS, 2) k_bwd_dq_bf16(BwdParams p) {
   const int a_base = tile_off(r32, hh);
   const int g_base = gather_base(lane);
 
-  const __bf16* kg = p.k + kh * p.kv_sh;
-  const __bf16* vg = p.v + kh * p.kv_sh;
+  const char* kg = reinterpret_cast<const char*>(p.k + kh * p.kv_sh);
+  const char* vg = reinterpret_cast<const char*>(p.v + kh * p.kv_sh);
+  const uint32_t kv_rowbytes = static_cast<uint32_t>(p.kv_ss) * 2;
+  const TileLane tl = tile_lane(wave, lane);
 
   // Q^T and dO^T operands: lane holds row qrow, columns 16 ks + 8 hh .. +7; lse' and D of that row
   bf16x8 qB[8], gB[8];
@@ -466,15 +436,22 @@ __global__ void __launch_bounds__(NTHREADS, 2) k_bwd_dq_bf16(BwdParams p) {
   const int k_end = p.causal ? min(p.s_k, q0 + BM) : p.s_k;
   const int ntiles = (k_end + BN - 1) / BN;
 
-  TileRegs tr;
-  tile_load(tr, kg, vg, p.kv_ss, 0, p.s_k, tid);
-  tile_store(tr, Ks, Vs, tid);
+  // K/V tiles go from global memory straight into LDS; key rows past s_k are clamped to the last
+  // row and masked below.  Tile t + 1 is on its way while tile t is computed on.
+  tile_dma(kg, kv_rowbytes, 0, p.s_k - 1, tl, smem, wave);
+  tile_dma(vg, kv_rowbytes, 0, p.s_k - 1, tl, smem + TILE_BYTES, wave);
+  lds_dma_wait();
   __syncthreads();
 
   for (int it = 0; it < ntiles; ++it) {
     const int k0 = it * BN;
-    const bool more = it + 1 < ntiles;
-    if (more) tile_load(tr, kg, vg, p.kv_ss, k0 + BN, p.s_k, tid);
+    const char* Ks = smem + (it & 1) * 2 * TILE_BYTES;
+    const char* Vs = Ks + TILE_BYTES;
+    if (it + 1 < ntiles) {
+      const char* Kn = smem + ((it + 1) & 1) * 2 * TILE_BYTES;
+      tile_dma(kg, kv_rowbytes, k0 + BN, p.s_k - 1, tl, Kn, wave);
+      tile_dma(vg, kv_rowbytes, k0 + BN, p.s_k - 1, tl, Kn + TILE_BYTES, wave);
+    }
 
     const bool active = !(p.causal && k0 > q0w + 31);
     if (active) {
@@ -533,8 +510,7 @@ __global__ void __launch_bounds__(NTHREADS, 2) k_bwd_dq_bf16(BwdParams p) {
         }
       }
     }
-    __syncthreads();
-    if (more) tile_store(tr, Ks, Vs, tid);
+    lds_dma_wait();
     __syncthreads();
   }
 
@@ -598,7 +574,16 @@ int launch_bwd_bf16(const dfa_shape& sh, const void* q, const void* k, const voi
     if (total > (1 << 30)) return DFA_ERR_SHAPE;
     b.total = static_cast<int>(total);
     b.per_xcd = (b.total + 7) / 8;
-    qs::k_bwd_dq_bf16<<<b.per_xcd * 8, NTHREADS, 2 * qs::TILE_BYTES, st>>>(b);
+    const size_t smem = 4 * qs::TILE_BYTES;
+    static bool attr_set = false;
+    if (!attr_set) {
+      const int rc = hip_status(hipFuncSetAttribute(reinterpret_cast<const void*>(qs::k_bwd_dq_bf16),
+                                                    hipFuncAttributeMaxDynamicSharedMemorySize,
+                                                    static_cast<int>(smem)));
+      if (rc) return rc;
+      attr_set = true;
+    }
+    qs::k_bwd_dq_bf16<<<b.per_xcd * 8, NTHREADS, smem, st>>>(b);
   }
   return last_launch_status();
 }

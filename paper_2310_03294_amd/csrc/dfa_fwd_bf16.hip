@@ -7,8 +7,9 @@
 // scores of ONE query: the running row maximum / row sum of the online softmax are then
 // per-lane scalars plus one exchange between lane l and l+32.  The exponentiated tile is fed
 // straight back, from registers, as the B operand of O^T += V^T P^T.
-// Q stays in registers for the whole kernel; K is read from LDS with ds_read_b128, V with the
-// transposing ds_read_b64_tr_b16.  The causal mask is applied only on tiles that straddle the
+// Q stays in registers for the whole kernel; K/V tiles are copied from global memory straight
+// into LDS (double-buffered); K is read from LDS with ds_read_b128, V with the transposing
+// ds_read_b64_tr_b16.  The causal mask is applied only on tiles that straddle the
 // diagonal; tiles above it are skipped.
 #include "dfa_internal.h"
 #include "dfa_mfma.h"
@@ -30,36 +31,6 @@ struct FwdParams {
   float scale;
   int64_t q_sh, q_ss, kv_sh, kv_ss, o_sh, o_ss, l_sh;
 };
-
-struct TileRegs { uint4 k[4], v[4]; };
-
-__device__ __forceinline__ void tile_load(TileRegs& t, const __bf16* kg, const __bf16* vg, int64_t ss,
-                                          int k0, int s_k, int tid) {
-  const int c = tid & 15;
-#pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    const int r = (tid >> 4) + 16 * i;
-    if (k0 + r < s_k) {
-      const int64_t off = static_cast<int64_t>(k0 + r) * ss + c * 8;
-      t.k[i] = *reinterpret_cast<const uint4*>(kg + off);
-      t.v[i] = *reinterpret_cast<const uint4*>(vg + off);
-    } else {
-      t.k[i] = make_uint4(0, 0, 0, 0);
-      t.v[i] = make_uint4(0, 0, 0, 0);
-    }
-  }
-}
-
-__device__ __forceinline__ void tile_store(const TileRegs& t, char* Ks, char* Vs, int tid) {
-  const int c = tid & 15;
-#pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    const int r = (tid >> 4) + 16 * i;
-    const int off = tile_off(r, c);
-    *reinterpret_cast<uint4*>(Ks + off) = t.k[i];
-    *reinterpret_cast<uint4*>(Vs + off) = t.v[i];
-  }
-}
 
 __global__ void __launch_bounds__(NTHREADS, 2) k_fwd_bf16(FwdParams p) {
   extern __shared__ __align__(16) char smem[];   // two (K tile, V tile) buffers
@@ -84,8 +55,10 @@ __global__ void __launch_bounds__(NTHREADS, 2) k_fwd_bf16(FwdParams p) {
   const int a_base = tile_off(r32, hh);     // per-lane LDS bases; the rest of every address is constant
   const int g_base = gather_base(lane);
 
-  const __bf16* kg = p.k + kh * p.kv_sh;
-  const __bf16* vg = p.v + kh * p.kv_sh;
+  const char* kg = reinterpret_cast<const char*>(p.k + kh * p.kv_sh);
+  const char* vg = reinterpret_cast<const char*>(p.v + kh * p.kv_sh);
+  const uint32_t kv_rowbytes = static_cast<uint32_t>(p.kv_ss) * 2;
+  const TileLane tl = tile_lane(wave, lane);
 
   // Q^T operand: lane holds Q[qrow][16 ks + 8 hh .. +7]
   bf16x8 qreg[8];
@@ -111,9 +84,11 @@ __global__ void __launch_bounds__(NTHREADS, 2) k_fwd_bf16(FwdParams p) {
   const int k_end = p.causal ? min(p.s_k, q0 + BM) : p.s_k;
   const int ntiles = (k_end + BN - 1) / BN;
 
-  TileRegs tr;
-  tile_load(tr, kg, vg, p.kv_ss, 0, p.s_k, tid);
-  tile_store(tr, smem, smem + TILE_BYTES, tid);
+  // K/V tiles go from global memory straight into LDS; key rows past s_k are clamped to the last
+  // row and masked below.  Tile t + 1 is on its way while tile t is computed on.
+  tile_dma(kg, kv_rowbytes, 0, p.s_k - 1, tl, smem, wave);
+  tile_dma(vg, kv_rowbytes, 0, p.s_k - 1, tl, smem + TILE_BYTES, wave);
+  lds_dma_wait();
   __syncthreads();
 
   // Online softmax of one 32-key block (exp2 domain, scores scaled by scale*log2 e), with a lazy
@@ -169,8 +144,11 @@ __global__ void __launch_bounds__(NTHREADS, 2) k_fwd_bf16(FwdParams p) {
     const int boff = (it & 1) * 2 * TILE_BYTES;
     const char* Ks = smem + boff;
     const char* Vs = Ks + TILE_BYTES;
-    char* Kn = smem + (2 * TILE_BYTES - boff);
-    if (more) tile_load(tr, kg, vg, p.kv_ss, k0 + BN, p.s_k, tid);
+    if (more) {
+      const char* Kn = smem + (2 * TILE_BYTES - boff);
+      tile_dma(kg, kv_rowbytes, k0 + BN, p.s_k - 1, tl, Kn, wave);
+      tile_dma(vg, kv_rowbytes, k0 + BN, p.s_k - 1, tl, Kn + TILE_BYTES, wave);
+    }
 
     const bool active = !(p.causal && k0 > q0w + 31);
     if (active) {
@@ -248,7 +226,7 @@ __global__ void __launch_bounds__(NTHREADS, 2) k_fwd_bf16(FwdParams p) {
         DFA_SCHED_FENCE();
       }
     }
-    if (more) tile_store(tr, Kn, Kn + TILE_BYTES, tid);
+    lds_dma_wait();
     __syncthreads();
   }
 

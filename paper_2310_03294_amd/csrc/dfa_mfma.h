@@ -122,6 +122,56 @@ __device__ __forceinline__ bf16x8 lds_gather(const char* base, int off) {
   return __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
 }
 
+// ---- global memory -> LDS tile copy without a register stop-over --------------------------
+// global_load_lds_dwordx4: every lane supplies its own global address and the wavefront's
+// 64 x 16 bytes land contiguously at the LDS byte address held in M0.  A padded 64-row tile
+// (64 x kRowBytes = 17 KB) is 17 such 1 KB pieces; of 4 copying wavefronts, wavefront w moves
+// pieces w, w + 4, w + 8, w + 12 and (w = 0 only) 16.  Byte 16 s of the tile is chunk s % 17 of
+// physical row s / 17; chunk 16 is the row's pad and receives a copy of chunk 15.
+//
+// The copy is issued from inline assembly, so the compiler neither sees it nor waits for it:
+// lds_dma_wait() before the barrier that publishes the tile is the caller's duty.  (Compiler-
+// tracked loads stay correct next to it: extra loads in flight only make its waits stricter.)
+struct TileLane { int row[5]; uint32_t cb[5]; };   // this lane's logical tile row and byte in the row, per piece
+
+__device__ __forceinline__ TileLane tile_lane(int w, int lane) {
+  TileLane m;
+#pragma unroll
+  for (int j = 0; j < 5; ++j) {
+    const int s = (w + 4 * j) * 64 + lane;
+    m.row[j] = prow(s / 17);                       // prow is its own inverse
+    const int c = s % 17;
+    m.cb[j] = static_cast<uint32_t>(c < 15 ? c : 15) * 16;
+  }
+  return m;
+}
+
+__device__ __forceinline__ uint32_t lds_addr(const char* p) {
+  return static_cast<uint32_t>(reinterpret_cast<uintptr_t>((DFA_LDS const char*)p));
+}
+
+// gbase and lds must be wave-uniform; voff is this lane's byte offset from gbase.
+__device__ __forceinline__ void lds_dma16(const char* gbase, uint32_t voff, uint32_t lds) {
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
+               :: "s"(lds), "v"(voff), "s"(gbase) : "memory", "m0");
+}
+
+// Rows row0 .. row0 + 63 of a [rows, d = 128] bf16 matrix at gbase (row pitch rowbytes) into the
+// padded LDS tile at `tile`; rows past `last` are clamped to it (callers mask them).
+__device__ __forceinline__ void tile_dma(const char* gbase, uint32_t rowbytes, int row0, int last,
+                                         const TileLane& m, const char* tile, int w) {
+  const uint32_t base = lds_addr(tile);
+#pragma unroll
+  for (int j = 0; j < 5; ++j) {
+    if (j < 4 || w == 0) {
+      const int r = row0 + m.row[j];
+      lds_dma16(gbase, static_cast<uint32_t>(r < last ? r : last) * rowbytes + m.cb[j], base + (w + 4 * j) * 1024);
+    }
+  }
+}
+
+__device__ __forceinline__ void lds_dma_wait() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
+
 __device__ __forceinline__ bf16x8 pack8(const f32x16& v, int first) {
   bf16x8 r;
 #pragma unroll
