@@ -82,6 +82,9 @@ FAKE = 4096  # non-null, 16-byte aligned, never dereferenced: validation fails b
     (dict(causal=1, s_k=128), -4), (dict(causal=2), -4), (dict(scale=0.0), -4), (dict(scale=float("nan")), -4),
     (dict(reserved=1), -4), (dict(q_stride_s=60), -2), (dict(kv_stride_s=63), -2), (dict(o_stride_h=12), -2),
     (dict(lse_stride_h=32), -2), (dict(dtype=B.DFA_BF16, d=64), -2),
+    # one head's slice of a chunk is addressed with 32-bit byte offsets: rows * row stride * 4 < 2^31
+    (dict(s_q=1 << 20, lse_stride_h=1 << 20, q_stride_s=512, q_stride_h=1 << 29), -2),
+    (dict(s_k=1 << 21, kv_stride_s=256, kv_stride_h=1 << 29), -2),
 ])
 def test_fwd_argument_errors(lib, kw, code):
     sh = _shape(**kw)
