@@ -3,8 +3,9 @@
 
 One "step" = one pass of the whole hot path for the heaviest worker (worker P-1) of the
 Llama-7B attention shape at N = 32768, P = 8 (chunk 4096, 32 heads x d128, bf16): the causal
-diagonal chunk, its four OWN off-diagonal pairs with their merges, the merges of the three
-partials that helpers send, the D pre-pass and the backward of the same five pairs.
+diagonal chunk, its four OWN off-diagonal pairs (each continuing from the running (O, lse)
+state: dfa_chunk_fwd_acc), the merges of the three partials that helpers send, the D pre-pass and
+the backward of the same five pairs.
 Inputs are resident in HBM before the timed region; the helpers' partials are produced
 beforehand (they arrive over the network in the distributed setting).
 
@@ -193,7 +194,7 @@ def main():
                                       "algorithmic_tflops": round(dq_fl / (dq_ms * 1e-3) / 1e12, 2),
                                       "executed_tflops": round(3.0 * dq_fl / (dq_ms * 1e-3) / 1e12, 2),
                                       "share_of_step": round(dq_ms / args.steps / ms, 3)},
-                    "forward (k_fwd_bf16 x5 + k_merge x7)": {"ms_per_step": round(fw_ms / fw_n, 4),
+                    f"forward (k_fwd_bf16 x{len(pairs)} + k_merge x{len(remote)})": {"ms_per_step": round(fw_ms / fw_n, 4),
                                                             "tflops": round(fw_fl / (fw_ms * 1e-3) / 1e12, 2),
                                                             "share_of_step": round(fw_ms / args.steps / ms, 3)}}}
 

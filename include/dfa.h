@@ -86,6 +86,19 @@ int dfa_chunk_fwd(const dfa_shape* sh, const void* q, const void* k, const void*
                   void* o, float* lse, void* stream);
 
 /*
+ * dfa_chunk_fwd_acc - attn(q_p, k_r, v_r, o, s) as the schedules call it (Algorithms 1-2): the
+ * same computation as dfa_chunk_fwd, started from the state the earlier key/value chunks left
+ * in (o, lse) instead of the empty state, and written back IN PLACE.  The state is exchanged
+ * as the normalised output and its logsumexp, i.e. the running (o, m, l) with m = lse, l = 1;
+ * the result equals dfa_chunk_fwd into a fresh buffer followed by dfa_merge (up to rounding),
+ * without the partial output's trip through memory.  (o = anything, lse = -inf) is the empty
+ * state.  s_k == 0 leaves (o, lse) untouched.  Arguments as dfa_chunk_fwd; o and lse are read
+ * and written.
+ */
+int dfa_chunk_fwd_acc(const dfa_shape* sh, const void* q, const void* k, const void* v,
+                      void* o, float* lse, void* stream);
+
+/*
  * dfa_merge - the rescale(o, s, o', s') update of the balanced schedule (Section 3.2,
  * Algorithm 2): exact combination of two partial results for the same query rows,
  *   lse = log(e^lse_a + e^lse_b),  o = e^(lse_a-lse) o_a + e^(lse_b-lse) o_b,

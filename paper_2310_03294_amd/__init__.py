@@ -9,6 +9,7 @@ from .binding import (  # noqa: F401
     Step,
     dfa_chunk_bwd,
     dfa_chunk_fwd,
+    dfa_chunk_fwd_acc,
     dfa_delta,
     dfa_merge,
     dfa_schedule,

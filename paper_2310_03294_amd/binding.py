@@ -51,7 +51,7 @@ class DfaStep(ctypes.Structure):
 
 Step = collections.namedtuple("Step", "t kind q_chunk kv_chunk send_to recv_from")
 
-EXPORTS = ("dfa_chunk_fwd", "dfa_merge", "dfa_delta", "dfa_chunk_bwd", "dfa_schedule",
+EXPORTS = ("dfa_chunk_fwd", "dfa_chunk_fwd_acc", "dfa_merge", "dfa_delta", "dfa_chunk_bwd", "dfa_schedule",
            "dfa_schedule_mode", "dfa_status_str", "dfa_version")
 
 
@@ -72,6 +72,7 @@ def load_library():
     vp, i32, i64 = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64
     shp = ctypes.POINTER(DfaShape)
     lib.dfa_chunk_fwd.argtypes = [shp, vp, vp, vp, vp, vp, vp]
+    lib.dfa_chunk_fwd_acc.argtypes = [shp, vp, vp, vp, vp, vp, vp]
     lib.dfa_merge.argtypes = [ctypes.POINTER(DfaMergeDesc), vp, vp, vp, vp, vp]
     lib.dfa_delta.argtypes = [shp, vp, vp, vp, vp]
     lib.dfa_chunk_bwd.argtypes = [shp, vp, vp, vp, vp, vp, vp, vp, vp, vp, ctypes.c_int, vp]
@@ -158,6 +159,19 @@ def dfa_chunk_fwd(q, k, v, causal, scale, o=None, lse=None, o_dtype=torch.float3
     sh = _make_shape(q, k, causal, scale, _dt(q), o=o, o_dtype=_dt(o), lse=lse)
     _check(lib.dfa_chunk_fwd(ctypes.byref(sh), q.data_ptr(), k.data_ptr(), v.data_ptr(),
                              o.data_ptr(), lse.data_ptr(), _stream(stream)), "dfa_chunk_fwd")
+    return o, lse
+
+
+def dfa_chunk_fwd_acc(q, k, v, causal, scale, o, lse, stream=None):
+    """attn(q_p, k_r, v_r, o, s): continues from the state in (o, lse), updates both in place."""
+    lib = load_library()
+    if v.shape != k.shape or v.stride() != k.stride():
+        raise ValueError("k and v must share shape and strides")
+    if lse.stride(1) != 1:
+        raise ValueError("lse must have unit innermost stride")
+    sh = _make_shape(q, k, causal, scale, _dt(q), o=o, o_dtype=_dt(o), lse=lse)
+    _check(lib.dfa_chunk_fwd_acc(ctypes.byref(sh), q.data_ptr(), k.data_ptr(), v.data_ptr(),
+                                 o.data_ptr(), lse.data_ptr(), _stream(stream)), "dfa_chunk_fwd_acc")
     return o, lse
 
 

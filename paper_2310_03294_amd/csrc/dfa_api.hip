@@ -47,8 +47,9 @@ extern "C" const char* dfa_status_str(int s) {
 
 extern "C" int dfa_version(void) { return 100; }
 
-extern "C" int dfa_chunk_fwd(const dfa_shape* sh, const void* q, const void* k, const void* v,
-                             void* o, float* lse, void* stream) {
+namespace {
+int chunk_fwd(const dfa_shape* sh, const void* q, const void* k, const void* v,
+              void* o, float* lse, int accumulate, void* stream) {
   int rc = check_common(sh);
   if (rc != DFA_OK) return rc;
   const bool have_kv = sh->s_k > 0;   // an empty key/value chunk may come with NULL k, v
@@ -61,11 +62,22 @@ extern "C" int dfa_chunk_fwd(const dfa_shape* sh, const void* q, const void* k, 
   if (sh->lse_stride_h < sh->s_q) return DFA_ERR_SHAPE;
   hipStream_t st = static_cast<hipStream_t>(stream);
   if (sh->s_q == 0) return DFA_OK;
-  if (sh->s_k == 0) return dfa::launch_fill_empty_fwd(*sh, o, lse, st);
+  if (sh->s_k == 0) return accumulate ? DFA_OK : dfa::launch_fill_empty_fwd(*sh, o, lse, st);
   if (sh->dtype == DFA_F32)
     return dfa::launch_fwd_f32(*sh, static_cast<const float*>(q), static_cast<const float*>(k),
-                               static_cast<const float*>(v), o, lse, st);
-  return dfa::launch_fwd_bf16(*sh, q, k, v, o, lse, st);
+                               static_cast<const float*>(v), o, lse, accumulate, st);
+  return dfa::launch_fwd_bf16(*sh, q, k, v, o, lse, accumulate, st);
+}
+}  // namespace
+
+extern "C" int dfa_chunk_fwd(const dfa_shape* sh, const void* q, const void* k, const void* v,
+                             void* o, float* lse, void* stream) {
+  return chunk_fwd(sh, q, k, v, o, lse, 0, stream);
+}
+
+extern "C" int dfa_chunk_fwd_acc(const dfa_shape* sh, const void* q, const void* k, const void* v,
+                                 void* o, float* lse, void* stream) {
+  return chunk_fwd(sh, q, k, v, o, lse, 1, stream);
 }
 
 extern "C" int dfa_merge(const dfa_merge_desc* md, void* o_a, float* lse_a,

@@ -50,12 +50,28 @@ __global__ void __launch_bounds__(kThreads) k_fwd_f32(F32Params p) {
   const float* vg = p.v + kh * p.kv_sh;
 
   load_tile<D, BQ, LD>(Qs, qg, p.q_ss, q0, p.s_q);
-  if (tid < BQ) { row_m[tid] = -INFINITY; row_l[tid] = 0.f; }
+  // Empty state, or (accumulate) the state of the earlier key/value chunks: the normalised output
+  // with its logsumexp is the running (o, m, l) with m = lse and l = 1.
+  if (tid < BQ) {
+    float m0 = -INFINITY;
+    if (p.accumulate && q0 + tid < p.s_q) m0 = p.lse[h * p.l_sh + q0 + tid];
+    row_m[tid] = m0; row_l[tid] = m0 > -INFINITY ? 1.f : 0.f;
+  }
   float acc[4][NC];
 #pragma unroll
-  for (int a = 0; a < 4; ++a)
+  for (int a = 0; a < 4; ++a) {
+    const int qi = q0 + ty * 4 + a;
+    const bool have = p.accumulate && qi < p.s_q && p.lse[h * p.l_sh + qi] > -INFINITY;
 #pragma unroll
-    for (int c = 0; c < NC; ++c) acc[a][c] = 0.f;
+    for (int c = 0; c < NC; ++c) {
+      float x = 0.f;
+      if (have) {
+        const int64_t off = h * p.o_sh + static_cast<int64_t>(qi) * p.o_ss + tx + 16 * c;
+        x = p.o_bf16 ? static_cast<float>(static_cast<const __bf16*>(p.o)[off]) : static_cast<const float*>(p.o)[off];
+      }
+      acc[a][c] = x;
+    }
+  }
 
   const int k_end = p.causal ? min(p.s_k, q0 + BQ) : p.s_k;
   for (int k0 = 0; k0 < k_end; k0 += BK) {
@@ -293,9 +309,9 @@ int set_smem(K kernel, size_t bytes) {
 }  // namespace
 
 int launch_fwd_f32(const dfa_shape& sh, const float* q, const float* k, const float* v,
-                   void* o, float* lse, hipStream_t st) {
+                   void* o, float* lse, int accumulate, hipStream_t st) {
   F32Params p = make_params(sh);
-  p.q = q; p.k = k; p.v = v; p.o = o; p.lse = lse;
+  p.q = q; p.k = k; p.v = v; p.o = o; p.lse = lse; p.accumulate = accumulate;
   dim3 grid((sh.s_q + 63) / 64, sh.h_q);
   const int D = sh.d;
   const size_t smem = sizeof(float) * (3 * 64 * (D + 4) + 64 * 65 + 3 * 64);

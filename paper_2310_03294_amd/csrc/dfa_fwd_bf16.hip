@@ -27,7 +27,7 @@ constexpr float LOG2E = 1.4426950408889634f;
 struct FwdParams {
   const __bf16 *q, *k, *v;
   void* o; float* lse;
-  int s_q, s_k, h_q, group, causal, o_bf16, ntq, total, per_xcd;
+  int s_q, s_k, h_q, group, causal, o_bf16, accumulate, ntq, total, per_xcd;
   float scale;
   int64_t q_sh, q_ss, kv_sh, kv_ss, o_sh, o_ss, l_sh;
 };
@@ -80,6 +80,30 @@ __global__ void __launch_bounds__(NTHREADS, 2) k_fwd_bf16(FwdParams p) {
   float m_run = -INFINITY;     // running maximum of the raw scores q.k
   float l_run = 0.f;           // this lane's half of the running row sum
   const float c2 = p.scale * LOG2E;
+  if (p.accumulate && qvalid) {
+    // State of the earlier key/value chunks: the normalised output with its logsumexp is the
+    // running (o, m, l) with m = lse (in raw-score units: lse / scale) and l = 1.
+    const float L = p.lse[head * p.l_sh + qrow];
+    if (L > -INFINITY) {
+      m_run = L / p.scale;
+      l_run = hh == 0 ? 1.f : 0.f;
+      const int64_t obase = head * p.o_sh + static_cast<int64_t>(qrow) * p.o_ss;
+#pragma unroll
+      for (int db = 0; db < 4; ++db)
+#pragma unroll
+        for (int g4 = 0; g4 < 4; ++g4) {
+          const int col = db * 32 + g4 * 8 + hh * 4;
+          if (p.o_bf16) {
+            const bf16x4 b = *reinterpret_cast<const bf16x4*>(static_cast<const __bf16*>(p.o) + obase + col);
+#pragma unroll
+            for (int e = 0; e < 4; ++e) o[db][g4 * 4 + e] = static_cast<float>(b[e]);
+          } else {
+            const float4 x = *reinterpret_cast<const float4*>(static_cast<const float*>(p.o) + obase + col);
+            o[db][g4 * 4] = x.x; o[db][g4 * 4 + 1] = x.y; o[db][g4 * 4 + 2] = x.z; o[db][g4 * 4 + 3] = x.w;
+          }
+        }
+    }
+  }
 
   const int k_end = p.causal ? min(p.s_k, q0 + BM) : p.s_k;
   const int ntiles = (k_end + BN - 1) / BN;
@@ -257,12 +281,12 @@ __global__ void __launch_bounds__(NTHREADS, 2) k_fwd_bf16(FwdParams p) {
 }  // namespace
 
 int launch_fwd_bf16(const dfa_shape& sh, const void* q, const void* k, const void* v,
-                    void* o, float* lse, hipStream_t st) {
+                    void* o, float* lse, int accumulate, hipStream_t st) {
   FwdParams p{};
   p.q = static_cast<const __bf16*>(q); p.k = static_cast<const __bf16*>(k); p.v = static_cast<const __bf16*>(v);
   p.o = o; p.lse = lse;
   p.s_q = sh.s_q; p.s_k = sh.s_k; p.h_q = sh.h_q; p.group = sh.h_q / sh.h_kv; p.causal = sh.causal;
-  p.o_bf16 = sh.o_dtype == DFA_BF16; p.scale = sh.scale;
+  p.o_bf16 = sh.o_dtype == DFA_BF16; p.scale = sh.scale; p.accumulate = accumulate;
   p.q_sh = sh.q_stride_h; p.q_ss = sh.q_stride_s; p.kv_sh = sh.kv_stride_h; p.kv_ss = sh.kv_stride_s;
   p.o_sh = sh.o_stride_h; p.o_ss = sh.o_stride_s; p.l_sh = sh.lse_stride_h;
   p.ntq = (sh.s_q + BM - 1) / BM;

@@ -16,14 +16,15 @@ int launch_fill_zero_rows(float* p, int heads, int rows, int d, int64_t stride_h
                           hipStream_t st);
 int launch_fill_empty_fwd(const dfa_shape& sh, void* o, float* lse, hipStream_t st);
 
+// accumulate != 0: (o, lse) hold the state of earlier key/value chunks on entry and are updated in place
 int launch_fwd_f32(const dfa_shape& sh, const float* q, const float* k, const float* v,
-                   void* o, float* lse, hipStream_t st);
+                   void* o, float* lse, int accumulate, hipStream_t st);
 int launch_bwd_f32(const dfa_shape& sh, const float* q, const float* k, const float* v,
                    const float* lse, const float* delta, const float* dO,
                    float* dq, float* dk, float* dv, int accumulate, hipStream_t st);
 
 int launch_fwd_bf16(const dfa_shape& sh, const void* q, const void* k, const void* v,
-                    void* o, float* lse, hipStream_t st);
+                    void* o, float* lse, int accumulate, hipStream_t st);
 int launch_bwd_bf16(const dfa_shape& sh, const void* q, const void* k, const void* v,
                     const float* lse, const float* delta, const void* dO,
                     float* dq, float* dk, float* dv, int accumulate, hipStream_t st);

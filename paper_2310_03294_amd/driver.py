@@ -33,10 +33,12 @@ def _chunk(t, i, c):
     return t[:, i * c:(i + 1) * c]
 
 
-def forward_worker(Q, K, V, scale, P, w, bufs: Buffers, remote=None, mode="balanced"):
-    """Forward share of worker w: its diagonal chunk, its OWN pairs merged into (O_w, L_w),
+def forward_worker(Q, K, V, scale, P, w, bufs: Buffers, remote=None, mode="balanced", fused=True):
+    """Forward share of worker w: its diagonal chunk, its OWN pairs folded into (O_w, L_w),
     the partials that arrive from helpers (`remote`: {helper_id: (o, lse)}) merged at the step
     they arrive, and its HELP pairs computed into fresh partial buffers.
+    fused: OWN pairs continue from the state in (O_w, L_w) (dfa_chunk_fwd_acc, the attn(q, k, v,
+    o, s) call of Algorithms 1-2); otherwise each is a partial result plus a dfa_merge.
     Returns {owner_id: (o_part, lse_part)} for the HELP pairs this worker computed."""
     c = bufs.c
     sent = {}
@@ -44,6 +46,9 @@ def forward_worker(Q, K, V, scale, P, w, bufs: Buffers, remote=None, mode="balan
     for st in B.dfa_schedule(P, w, mode):
         if st.kind == B.DFA_STEP_DIAG:
             B.dfa_chunk_fwd(_chunk(Q, w, c), _chunk(K, w, c), _chunk(V, w, c), True, scale, o=o_w, lse=l_w)
+        elif st.kind == B.DFA_STEP_OWN and fused:
+            B.dfa_chunk_fwd_acc(_chunk(Q, w, c), _chunk(K, st.kv_chunk, c), _chunk(V, st.kv_chunk, c), False, scale,
+                                o_w, l_w)
         elif st.kind == B.DFA_STEP_OWN:
             po, pl = bufs.part_o[0], bufs.part_l[0]
             B.dfa_chunk_fwd(_chunk(Q, w, c), _chunk(K, st.kv_chunk, c), _chunk(V, st.kv_chunk, c), False, scale,
@@ -77,11 +82,11 @@ def backward_worker(Q, K, V, dO, scale, P, w, bufs: Buffers, mode="balanced", wi
                         accumulate=True)
 
 
-def run_worker_share(Q, K, V, dO, scale, P, w, bufs: Buffers, remote):
+def run_worker_share(Q, K, V, dO, scale, P, w, bufs: Buffers, remote, fused=True):
     """One pass of worker w's whole share: forward (incl. merges of the helpers' partials),
     the D pre-pass and the backward of the same pairs.  Gradient buffers are accumulated into
     (callers zero them when they need the share's own sums)."""
-    forward_worker(Q, K, V, scale, P, w, bufs, remote=remote)
+    forward_worker(Q, K, V, scale, P, w, bufs, remote=remote, fused=fused)
     backward_worker(Q, K, V, dO, scale, P, w, bufs)
 
 
@@ -99,8 +104,9 @@ def helper_partials_for(Q, K, V, scale, P, w, bufs: Buffers):
     return out
 
 
-def run_all_workers(Q, K, V, dO, scale, P, bufs: Buffers, mode="balanced", backward=True):
-    """The whole schedule of all P workers, time step by time step, on one GPU."""
+def run_all_workers(Q, K, V, dO, scale, P, bufs: Buffers, mode="balanced", backward=True, fused=True):
+    """The whole schedule of all P workers, time step by time step, on one GPU.
+    fused: OWN pairs continue from the owner's state (dfa_chunk_fwd_acc) instead of partial + merge."""
     c = bufs.c
     scheds = [B.dfa_schedule(P, w, mode) for w in range(P)]
     nsteps = len(scheds[0])
@@ -111,6 +117,9 @@ def run_all_workers(Q, K, V, dO, scale, P, bufs: Buffers, mode="balanced", backw
             if st.kind == B.DFA_STEP_DIAG:
                 B.dfa_chunk_fwd(_chunk(Q, w, c), _chunk(K, w, c), _chunk(V, w, c), True, scale,
                                 o=_chunk(bufs.O, w, c), lse=_chunk(bufs.L, w, c))
+            elif st.kind == B.DFA_STEP_OWN and fused:
+                B.dfa_chunk_fwd_acc(_chunk(Q, w, c), _chunk(K, st.kv_chunk, c), _chunk(V, st.kv_chunk, c), False,
+                                    scale, _chunk(bufs.O, w, c), _chunk(bufs.L, w, c))
             elif st.kind == B.DFA_STEP_OWN:
                 po, pl = bufs.part_o[0], bufs.part_l[0]
                 B.dfa_chunk_fwd(_chunk(Q, w, c), _chunk(K, st.kv_chunk, c), _chunk(V, st.kv_chunk, c), False,

@@ -161,11 +161,11 @@ def test_empty_key_chunk_gives_merge_identity(dtype):
     assert torch.equal(o2, ref_o) and torch.equal(l2, ref_l)
 
 
-def _schedule_case(w: dfa_inputs.Workload, mode="balanced"):
+def _schedule_case(w: dfa_inputs.Workload, mode="balanced", fused=True):
     q, k, v, do = (dfa_inputs.full_sequence(w, t) for t in range(4))
     Q, K, V, dO = (t.to(dev()) for t in (q, k, v, do))
     bufs = driver.Buffers(w.h_q, w.h_kv, w.n_total, w.d, w.p, dev())
-    driver.run_all_workers(Q, K, V, dO, w.scale, w.p, bufs, mode=mode)
+    driver.run_all_workers(Q, K, V, dO, w.scale, w.p, bufs, mode=mode, fused=fused)
     torch.cuda.synchronize()
     q64, k64, v64, do64 = (np64(t) for t in (q, k, v, do))
     O, L = A.attention_fwd(q64, k64, v64, w.scale)
@@ -177,13 +177,16 @@ def _schedule_case(w: dfa_inputs.Workload, mode="balanced"):
     return errs
 
 
-def test_config1_full_balanced_schedule():
-    """Config 1: fp32, 1 head, d=64, N=1024, P=4; merged outputs of the whole schedule vs the monolithic oracle."""
-    _schedule_case(dfa_inputs.CONFIGS[0])
+@pytest.mark.parametrize("fused", [True, False])
+def test_config1_full_balanced_schedule(fused):
+    """Config 1: fp32, 1 head, d=64, N=1024, P=4; merged outputs of the whole schedule vs the monolithic oracle.
+    fused: OWN pairs continue from the owner's state (dfa_chunk_fwd_acc); else partial + dfa_merge."""
+    _schedule_case(dfa_inputs.CONFIGS[0], fused=fused)
 
 
-def test_config1_ring_schedule():
-    _schedule_case(dfa_inputs.CONFIGS[0], mode="ring")
+@pytest.mark.parametrize("fused", [True, False])
+def test_config1_ring_schedule(fused):
+    _schedule_case(dfa_inputs.CONFIGS[0], mode="ring", fused=fused)
 
 
 @pytest.mark.parametrize("P", [1, 2, 3, 5, 8])
@@ -191,3 +194,52 @@ def test_config1_ring_schedule():
 def test_balanced_schedule_odd_even_gqa(P, dtype):
     w = dfa_inputs.Workload(f"t_p{P}", 4, 2, 128, 192 * P, P, dtype, 4321 + P)
     _schedule_case(w)
+    if P in (3, 8):
+        _schedule_case(w, fused=False)
+
+
+@pytest.mark.parametrize("dtype,d,o_dtype", [(torch.float32, 64, torch.float32), (torch.float32, 128, torch.float32),
+                                             (torch.bfloat16, 128, torch.float32),
+                                             (torch.bfloat16, 128, torch.bfloat16)])
+def test_chunk_fwd_acc_chain(dtype, d, o_dtype):
+    """attn(q, k_r, v_r, o, s) over three key/value chunks of ragged sizes, started from the empty
+    state (lse = -inf over a poisoned o): equals attention over the concatenated keys (oracle), and
+    equals partial + merge up to rounding; an empty chunk leaves the state untouched."""
+    h_q, h_kv, s_q = 4, 2, 200
+    sizes = [200, 77, 130]            # the first chunk is the causal diagonal one
+    scale = 1 / math.sqrt(d)
+    g = torch.Generator().manual_seed(77)
+    q = torch.randn(h_q, s_q, d, generator=g).to(dtype)
+    ks = [torch.randn(h_kv, n, d, generator=g).to(dtype) for n in sizes]
+    vs = [torch.randn(h_kv, n, d, generator=g).to(dtype) for n in sizes]
+    Q = q.to(dev())
+    o = torch.full((h_q, s_q, d), float("nan"), dtype=o_dtype, device=dev())
+    lse = torch.full((h_q, s_q), -math.inf, device=dev())
+    o_m = l_m = None
+    for i, (k, v) in enumerate(zip(ks, vs)):
+        K, V = k.to(dev()), v.to(dev())
+        dfa.dfa_chunk_fwd_acc(Q, K, V, i == 0, scale, o, lse)
+        po, pl = dfa.dfa_chunk_fwd(Q, K, V, i == 0, scale, o_dtype=o_dtype)
+        if o_m is None:
+            o_m, l_m = po, pl
+        else:
+            dfa.dfa_merge(o_m, l_m, po, pl)
+    keep_o, keep_l = o.clone(), lse.clone()
+    empty = torch.empty(h_kv, 0, d, dtype=dtype, device=dev())
+    dfa.dfa_chunk_fwd_acc(Q, empty, empty, False, scale, o, lse)
+    torch.cuda.synchronize()
+    assert torch.equal(o, keep_o) and torch.equal(lse, keep_l)
+    # oracle: softmax over all visible keys (causal inside chunk 0, everything of chunks 1, 2)
+    q64 = np64(q); grp = h_q // h_kv
+    O = np.zeros((h_q, s_q, d)); L = np.zeros((h_q, s_q))
+    for h in range(h_q):
+        kh = h // grp
+        s = [scale * q64[h] @ np64(k)[kh].T for k in ks]
+        s[0] = np.where(np.arange(sizes[0])[None, :] <= np.arange(s_q)[:, None], s[0], -np.inf)
+        sc = np.concatenate(s, axis=1); vv = np.concatenate([np64(v)[kh] for v in vs], axis=0)
+        m = sc.max(1, keepdims=True); e = np.exp(sc - m); l = e.sum(1, keepdims=True)
+        O[h] = (e / l) @ vv; L[h] = (m + np.log(l))[:, 0]
+    tol = TOL[dtype] if o_dtype == torch.float32 else 2e-2
+    assert maxerr(o, O) <= tol and maxerr(lse, L) <= (1e-5 if dtype == torch.float32 else 2e-2)
+    assert maxerr(o, np64(o_m)) <= (2e-5 if (dtype == torch.float32) else 2e-2)
+    assert maxerr(lse, np64(l_m)) <= 1e-5
