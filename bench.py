@@ -143,26 +143,21 @@ def main():
         timed("forward", record, fwd_flops,
               lambda: driver.forward_worker(Q, K, V, w.scale, w.p, worker, bufs, remote=remote))
         B.dfa_delta(chunk(bufs.O, worker), chunk(dO, worker), delta=chunk(bufs.delta, worker))
+        seen_q, seen_kv = set(), set()     # first contribution to a gradient chunk overwrites, the rest accumulate
         for (qc, kc, kind) in pairs:
             n = c * (c + 1) // 2 if qc == kc else c * c
             common = (chunk(Q, qc), chunk(K, kc), chunk(V, kc), chunk(bufs.L, qc), chunk(bufs.delta, qc), chunk(dO, qc))
             diag = kind == B.DFA_STEP_DIAG
+            acc_kv, acc_q = kc in seen_kv, qc in seen_q
+            seen_kv.add(kc); seen_q.add(qc)
             # the two kernels of one dfa_chunk_bwd, launched through the same entry point one at a
             # time so that each gets its own event pair: S, dP, dV, dK = 8 d nnz; dQ (with S, dP
             # recomputed) = 2 d nnz algorithmic, 6 d nnz executed
             timed("k_bwd_dkdv_bf16", record, 8.0 * w.d * w.h_q * n,
                   lambda: B.dfa_chunk_bwd(*common, None, chunk(bufs.dK, kc), chunk(bufs.dV, kc), diag, w.scale,
-                                          accumulate=True))
+                                          accumulate=acc_kv))
             timed("k_bwd_dq_bf16", record, 2.0 * w.d * w.h_q * n,
-                  lambda: B.dfa_chunk_bwd(*common, chunk(bufs.dQ, qc), None, None, diag, w.scale, accumulate=True))
-
-    if args.calibrate_copy:
-        src = torch.zeros(1 << 28, dtype=torch.float32, device=dev)
-        dst = torch.empty_like(src)
-        torch.cuda.synchronize()
-        torch.add(src, 1.0, out=dst)     # one dispatch: 2^30 B read, 2^30 B written
-        torch.cuda.synchronize()
-        del src, dst
+                  lambda: B.dfa_chunk_bwd(*common, chunk(bufs.dQ, qc), None, None, diag, w.scale, accumulate=acc_q))
 
     for _ in range(args.warmup):
         step(False)

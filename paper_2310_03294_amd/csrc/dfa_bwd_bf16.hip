@@ -65,8 +65,8 @@ constexpr int SMEM_BYTES = OFF_PX + 2 * PX_BYTES;
 // LDS address in M0).  A padded tile is 17 such 1 KB pieces; S wavefront w moves pieces w, w + 4,
 // w + 8, w + 12 and (w = 0 only) 16.  Byte 16 s of the tile is chunk s % 17 of physical row
 // s / 17; chunk 16 is the pad (it receives a copy of chunk 15).  Only lse / D pass through a
-// register.  The dP wavefronts move nothing: the compiler makes a wavefront wait for its own
-// outstanding copies before its next transposing LDS read, which for them comes at once.
+// register.  The copies are issued from inline assembly (see lds_dma16): the S wavefronts, which
+// have slack, issue them at the top of a slot and wait for them just before the slot's barrier.
 struct QTileRegs { float ld; bool ld_ok; };
 
 struct QTileLane { int row[5]; uint32_t cb[5]; };   // this lane's logical tile row and byte in the row, per piece
@@ -99,25 +99,25 @@ __device__ __forceinline__ void qtile_advance(QTileCursor& cur, const BwdParams&
   }
 }
 
-__device__ __forceinline__ void dma16(const char* g, char* lds_uniform) {
-  __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)g,
-                                   (DFA_LDS void*)lds_uniform, 16, 0, 0);
-}
-
 // Rows past s_q are clamped to the last row instead of zero-filled: their lse' is +inf, so P and
 // dS vanish for them whatever (finite) Q and dO the tile holds.  Qs, Gs: LDS tiles to fill.
-__device__ __forceinline__ void qtile_load(QTileRegs& t, const QTileCursor& cur, const QTileLane& m,
-                                           const BwdParams& p, char* Qs, char* Gs, int wave, int tid) {
+__device__ __forceinline__ void qtile_copy(const QTileCursor& cur, const QTileLane& m, const BwdParams& p,
+                                           char* Qs, char* Gs, int wave) {
   const uint32_t rowbytes = static_cast<uint32_t>(p.q_ss) * 2;
   const int last = p.s_q - 1;
 #pragma unroll
   for (int j = 0; j < 5; ++j) {
     if (j < 4 || wave == 0) {
       const uint32_t off = static_cast<uint32_t>(min(cur.q0 + m.row[j], last)) * rowbytes + m.cb[j];
-      dma16(cur.qh + off, Qs + (wave + 4 * j) * 1024);
-      dma16(cur.gh + off, Gs + (wave + 4 * j) * 1024);
+      lds_dma16(cur.qh, off, lds_addr(Qs) + (wave + 4 * j) * 1024);
+      lds_dma16(cur.gh, off, lds_addr(Gs) + (wave + 4 * j) * 1024);
     }
   }
+}
+
+// lse (even wavefronts) or D (odd wavefronts) of the tile's 64 rows, one per lane, into a register.
+__device__ __forceinline__ void qtile_load_ld(QTileRegs& t, const QTileCursor& cur, const BwdParams& p, int tid) {
+  const int last = p.s_q - 1;
   const int r = cur.q0 + (tid & 63);
   t.ld_ok = r <= last;
   t.ld = cur.ldh[static_cast<uint32_t>(min(r, last))];
@@ -226,21 +226,32 @@ __global__ void __launch_bounds__(NT, 2) k_bwd_dkdv_bf16(BwdParams p) {
   const int ntq = (p.s_q - q_begin + BM - 1) / BM;  // query tiles per head for this key tile
   const int niter = ntq * p.group;
 
+  // Tile staging (S wavefronts only).  Two cursors: `cur` for the Q/dO copies (tile t + 1 during
+  // slot t), `curl` for lse / D, which pass through a register and run one tile further ahead.
+  // Order inside a slot: store the held lse / D, load the next ones, THEN issue the copies - the
+  // compiler knows nothing of the copies, so any wait it places for its own loads must come
+  // before them or it would wait for them too.
   QTileRegs tr;
-  QTileCursor cur;
+  QTileCursor cur, curl;
   {
     const int hq0 = kh * p.group;
     cur.qh = reinterpret_cast<const char*>(p.q + hq0 * p.q_sh);
     cur.gh = reinterpret_cast<const char*>(p.dO + hq0 * p.q_sh);
     cur.ldh = ((wave & 1) ? p.delta : p.lse) + hq0 * p.l_sh;
     cur.q0 = q_begin;
+    curl = cur;
   }
   const int q_end = q_begin + ntq * BM;
   const QTileLane tl = qtile_lane(kb, lane);
   if (!dp_wave) {
-    qtile_load(tr, cur, tl, p, smem + OFF_Q, smem + OFF_G, wave, tid);
+    qtile_load_ld(tr, curl, p, tid);
     qtile_store(tr, reinterpret_cast<float*>(smem + OFF_LD), tid);
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");     // this wavefront's copies into LDS have landed
+    if (niter > 1) {
+      qtile_advance(curl, p, q_begin, q_end);
+      qtile_load_ld(tr, curl, p, tid);           // lse / D of tile 1, stored in slot 0
+    }
+    qtile_copy(cur, tl, p, smem + OFF_Q, smem + OFF_G, wave);
+    lds_dma_wait();                                // this wavefront's copies into LDS have landed
   }
   __syncthreads();
 
@@ -250,16 +261,19 @@ __global__ void __launch_bounds__(NT, 2) k_bwd_dkdv_bf16(BwdParams p) {
   // the MFMAs of the other.  Both kinds run niter + 1 slots (the S wavefronts idle in the last,
   // the dP wavefronts have no dS/dK in the first); each kind has its own straight-line loop.
   int slot = 0;            // t % 3
-  // DFA_PREFETCH(IT, NEXT): start moving tile IT + 1 into its ring slots; DFA_COMMIT: lse / D.
-  // The copies into LDS are complete at the barrier that ends the slot (the barrier's release
-  // fence waits for them).
-#define DFA_PREFETCH(IT, NEXT)                                                                   \
+  // DFA_STAGE(IT, NEXT): lse / D of tile IT + 1 from the register into LDS, lse / D of tile IT + 2
+  // into the register, then the copies of tile IT + 1 into its ring slots.
+#define DFA_STAGE(IT, NEXT)                                                                      \
   {                                                                                              \
+    qtile_store(tr, reinterpret_cast<float*>(smem + OFF_LD + (NEXT) * LD_BYTES), tid);           \
+    if ((IT) + 2 < niter) {                                                                      \
+      qtile_advance(curl, p, q_begin, q_end);                                                    \
+      qtile_load_ld(tr, curl, p, tid);                                                           \
+    }                                                                                            \
     qtile_advance(cur, p, q_begin, q_end);                                                       \
-    qtile_load(tr, cur, tl, p, smem + OFF_Q + (NEXT) * QTILE_BYTES,                              \
-               smem + OFF_G + (((IT) + 1) & 1) * QTILE_BYTES, wave, tid);                        \
+    qtile_copy(cur, tl, p, smem + OFF_Q + (NEXT) * QTILE_BYTES,                                  \
+               smem + OFF_G + (((IT) + 1) & 1) * QTILE_BYTES, wave);                             \
   }
-#define DFA_COMMIT(NEXT) qtile_store(tr, reinterpret_cast<float*>(smem + OFF_LD + (NEXT) * LD_BYTES), tid);
 
   if (!dp_wave) {
     for (int it = 0; it < niter; ++it) {
@@ -269,7 +283,7 @@ __global__ void __launch_bounds__(NT, 2) k_bwd_dkdv_bf16(BwdParams p) {
       const char* Gs = smem + OFF_G + (it & 1) * QTILE_BYTES;
       const float* Ls = reinterpret_cast<const float*>(smem + OFF_LD + slot * LD_BYTES);
       const int q0 = q_begin + (it % ntq) * BM;
-      if (more) DFA_PREFETCH(it, next)
+      if (more) DFA_STAGE(it, next)
       f32x16 c0, c1;
       row_products(c0, c1, Qs, a_base, bT);          // S = Q K^T
       // Only the causal diagonal needs a mask: query rows past s_q carry lse' = +inf (P = 0)
@@ -301,8 +315,7 @@ __global__ void __launch_bounds__(NT, 2) k_bwd_dkdv_bf16(BwdParams p) {
         for (int j = 0; j < 4; ++j) *reinterpret_cast<bf16x8*>(px + j * 1024) = w[j >> 1][j & 1];
       }
       col_products(acc, Gs, g_base, w);              // dV^T += dO^T P
-      if (more) DFA_COMMIT(next)
-      asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // this wavefront's copies into LDS have landed
+      lds_dma_wait();                                // this wavefront's copies into LDS have landed
       __syncthreads();
       slot = next;
     }
@@ -347,8 +360,7 @@ __global__ void __launch_bounds__(NT, 2) k_bwd_dkdv_bf16(BwdParams p) {
     __syncthreads();
   }
 
-#undef DFA_PREFETCH
-#undef DFA_COMMIT
+#undef DFA_STAGE
 
   if (kvalid) {
     float* dst = (dp_wave ? p.dk : p.dv) + kh * p.dkv_sh + static_cast<int64_t>(kvrow) * p.dkv_ss;

@@ -64,11 +64,20 @@ def forward_worker(Q, K, V, scale, P, w, bufs: Buffers, remote=None, mode="balan
     return sent
 
 
-def backward_worker(Q, K, V, dO, scale, P, w, bufs: Buffers, mode="balanced", with_delta=True):
+def new_pass():
+    """Bookkeeping of one backward pass: which dQ / dK,dV chunks already hold a contribution.
+    The first contribution to a chunk overwrites it (no zero-fill, no read of stale values), the
+    later ones accumulate."""
+    return {"dq": set(), "dkv": set()}
+
+
+def backward_worker(Q, K, V, dO, scale, P, w, bufs: Buffers, mode="balanced", with_delta=True, touched=None):
     """Backward of the pairs worker w computed in the forward (same pair -> worker assignment),
     from the final merged O and L of each query chunk; nothing of the forward is re-run.
     For a HELP pair the logsumexp and D of the helped chunk must already be in `bufs`
-    (in the distributed setting they travel with that chunk's queries and dO)."""
+    (in the distributed setting they travel with that chunk's queries and dO).
+    touched: a new_pass() record shared by the calls of one pass; None = always accumulate into
+    what the gradient buffers hold."""
     c = bufs.c
     for st in B.dfa_schedule(P, w, mode):
         if st.kind == B.DFA_STEP_IDLE:
@@ -76,18 +85,27 @@ def backward_worker(Q, K, V, dO, scale, P, w, bufs: Buffers, mode="balanced", wi
         qc, kc = st.q_chunk, st.kv_chunk
         if with_delta and st.kind == B.DFA_STEP_DIAG:
             B.dfa_delta(_chunk(bufs.O, qc, c), _chunk(dO, qc, c), delta=_chunk(bufs.delta, qc, c))
-        B.dfa_chunk_bwd(_chunk(Q, qc, c), _chunk(K, kc, c), _chunk(V, kc, c), _chunk(bufs.L, qc, c),
-                        _chunk(bufs.delta, qc, c), _chunk(dO, qc, c), _chunk(bufs.dQ, qc, c),
-                        _chunk(bufs.dK, kc, c), _chunk(bufs.dV, kc, c), st.kind == B.DFA_STEP_DIAG, scale,
-                        accumulate=True)
+        args = (_chunk(Q, qc, c), _chunk(K, kc, c), _chunk(V, kc, c), _chunk(bufs.L, qc, c),
+                _chunk(bufs.delta, qc, c), _chunk(dO, qc, c))
+        diag = st.kind == B.DFA_STEP_DIAG
+        acc_q = touched is None or qc in touched["dq"]
+        acc_kv = touched is None or kc in touched["dkv"]
+        if acc_q == acc_kv:
+            B.dfa_chunk_bwd(*args, _chunk(bufs.dQ, qc, c), _chunk(bufs.dK, kc, c), _chunk(bufs.dV, kc, c), diag, scale,
+                            accumulate=acc_q)
+        else:   # one side starts fresh, the other accumulates: the two halves of the call, one after the other
+            B.dfa_chunk_bwd(*args, None, _chunk(bufs.dK, kc, c), _chunk(bufs.dV, kc, c), diag, scale, accumulate=acc_kv)
+            B.dfa_chunk_bwd(*args, _chunk(bufs.dQ, qc, c), None, None, diag, scale, accumulate=acc_q)
+        if touched is not None:
+            touched["dq"].add(qc); touched["dkv"].add(kc)
 
 
 def run_worker_share(Q, K, V, dO, scale, P, w, bufs: Buffers, remote, fused=True):
     """One pass of worker w's whole share: forward (incl. merges of the helpers' partials),
-    the D pre-pass and the backward of the same pairs.  Gradient buffers are accumulated into
-    (callers zero them when they need the share's own sums)."""
+    the D pre-pass and the backward of the same pairs.  The gradient chunks the share touches are
+    overwritten with the share's own sums (first contribution overwrites, the rest accumulate)."""
     forward_worker(Q, K, V, scale, P, w, bufs, remote=remote, fused=fused)
-    backward_worker(Q, K, V, dO, scale, P, w, bufs)
+    backward_worker(Q, K, V, dO, scale, P, w, bufs, touched=new_pass())
 
 
 def helper_partials_for(Q, K, V, scale, P, w, bufs: Buffers):
@@ -138,5 +156,6 @@ def run_all_workers(Q, K, V, dO, scale, P, bufs: Buffers, mode="balanced", backw
         # a helper's backward needs D of the chunk it helped, so all D vectors come first
         for w in range(P):
             B.dfa_delta(_chunk(bufs.O, w, c), _chunk(dO, w, c), delta=_chunk(bufs.delta, w, c))
+        touched = new_pass()
         for w in range(P):
-            backward_worker(Q, K, V, dO, scale, P, w, bufs, mode, with_delta=False)
+            backward_worker(Q, K, V, dO, scale, P, w, bufs, mode, with_delta=False, touched=touched)
