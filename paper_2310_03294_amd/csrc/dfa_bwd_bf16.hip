@@ -69,19 +69,6 @@ constexpr int SMEM_BYTES = OFF_PX + 2 * PX_BYTES;
 // have slack, issue them at the top of a slot and wait for them just before the slot's barrier.
 struct QTileRegs { float ld; bool ld_ok; };
 
-struct QTileLane { int row[5]; uint32_t cb[5]; };   // this lane's logical tile row and byte in the row, per piece
-
-__device__ __forceinline__ QTileLane qtile_lane(int wave, int lane) {
-  QTileLane m;
-#pragma unroll
-  for (int j = 0; j < 5; ++j) {
-    const int s = (wave + 4 * j) * 64 + lane;
-    m.row[j] = prow(s / 17);                       // prow is its own inverse
-    m.cb[j] = static_cast<uint32_t>(min(s % 17, 15)) * 16;
-  }
-  return m;
-}
-
 // Where the next (Q, dO, lse, D) tile comes from: wave-uniform head bases, advanced tile by
 // tile (no division in the loop), plus per-thread 32-bit byte offsets inside the head.
 struct QTileCursor {
@@ -101,18 +88,11 @@ __device__ __forceinline__ void qtile_advance(QTileCursor& cur, const BwdParams&
 
 // Rows past s_q are clamped to the last row instead of zero-filled: their lse' is +inf, so P and
 // dS vanish for them whatever (finite) Q and dO the tile holds.  Qs, Gs: LDS tiles to fill.
-__device__ __forceinline__ void qtile_copy(const QTileCursor& cur, const QTileLane& m, const BwdParams& p,
-                                           char* Qs, char* Gs, int wave) {
+__device__ __forceinline__ void qtile_copy(const QTileCursor& cur, const TileLane& m, const BwdParams& p,
+                                           char* Qs, char* Gs, int w, int lane) {
   const uint32_t rowbytes = static_cast<uint32_t>(p.q_ss) * 2;
-  const int last = p.s_q - 1;
-#pragma unroll
-  for (int j = 0; j < 5; ++j) {
-    if (j < 4 || wave == 0) {
-      const uint32_t off = static_cast<uint32_t>(min(cur.q0 + m.row[j], last)) * rowbytes + m.cb[j];
-      lds_dma16(cur.qh, off, lds_addr(Qs) + (wave + 4 * j) * 1024);
-      lds_dma16(cur.gh, off, lds_addr(Gs) + (wave + 4 * j) * 1024);
-    }
-  }
+  tile_dma(cur.qh, rowbytes, cur.q0, p.s_q - 1, m, Qs, w, lane);
+  tile_dma(cur.gh, rowbytes, cur.q0, p.s_q - 1, m, Gs, w, lane);
 }
 
 // lse (even wavefronts) or D (odd wavefronts) of the tile's 64 rows, one per lane, into a register.
@@ -242,7 +222,7 @@ __global__ void __launch_bounds__(NT, 2) k_bwd_dkdv_bf16(BwdParams p) {
     curl = cur;
   }
   const int q_end = q_begin + ntq * BM;
-  const QTileLane tl = qtile_lane(kb, lane);
+  const TileLane tl = tile_lane(kb, lane, static_cast<uint32_t>(p.q_ss) * 2);
   if (!dp_wave) {
     qtile_load_ld(tr, curl, p, tid);
     qtile_store(tr, reinterpret_cast<float*>(smem + OFF_LD), tid);
@@ -250,7 +230,7 @@ __global__ void __launch_bounds__(NT, 2) k_bwd_dkdv_bf16(BwdParams p) {
       qtile_advance(curl, p, q_begin, q_end);
       qtile_load_ld(tr, curl, p, tid);           // lse / D of tile 1, stored in slot 0
     }
-    qtile_copy(cur, tl, p, smem + OFF_Q, smem + OFF_G, wave);
+    qtile_copy(cur, tl, p, smem + OFF_Q, smem + OFF_G, kb, lane);
     lds_dma_wait();                                // this wavefront's copies into LDS have landed
   }
   __syncthreads();
@@ -272,7 +252,7 @@ __global__ void __launch_bounds__(NT, 2) k_bwd_dkdv_bf16(BwdParams p) {
     }                                                                                            \
     qtile_advance(cur, p, q_begin, q_end);                                                       \
     qtile_copy(cur, tl, p, smem + OFF_Q + (NEXT) * QTILE_BYTES,                                  \
-               smem + OFF_G + (((IT) + 1) & 1) * QTILE_BYTES, wave);                             \
+               smem + OFF_G + (((IT) + 1) & 1) * QTILE_BYTES, kb, lane);                         \
   }
 
   if (!dp_wave) {
@@ -416,7 +396,7 @@ __global__ void __launch_bounds__(NTHREADS, 2) k_bwd_dq_bf16(BwdParams p) {
   const char* kg = reinterpret_cast<const char*>(p.k + kh * p.kv_sh);
   const char* vg = reinterpret_cast<const char*>(p.v + kh * p.kv_sh);
   const uint32_t kv_rowbytes = static_cast<uint32_t>(p.kv_ss) * 2;
-  const TileLane tl = tile_lane(wave, lane);
+  const TileLane tl = tile_lane(wave, lane, kv_rowbytes);
 
   // Q^T and dO^T operands: lane holds row qrow, columns 16 ks + 8 hh .. +7; lse' and D of that row
   bf16x8 qB[8], gB[8];
@@ -450,8 +430,8 @@ __global__ void __launch_bounds__(NTHREADS, 2) k_bwd_dq_bf16(BwdParams p) {
 
   // K/V tiles go from global memory straight into LDS; key rows past s_k are clamped to the last
   // row and masked below.  Tile t + 1 is on its way while tile t is computed on.
-  tile_dma(kg, kv_rowbytes, 0, p.s_k - 1, tl, smem, wave);
-  tile_dma(vg, kv_rowbytes, 0, p.s_k - 1, tl, smem + TILE_BYTES, wave);
+  tile_dma(kg, kv_rowbytes, 0, p.s_k - 1, tl, smem, wave, lane);
+  tile_dma(vg, kv_rowbytes, 0, p.s_k - 1, tl, smem + TILE_BYTES, wave, lane);
   lds_dma_wait();
   __syncthreads();
 
@@ -461,8 +441,8 @@ __global__ void __launch_bounds__(NTHREADS, 2) k_bwd_dq_bf16(BwdParams p) {
     const char* Vs = Ks + TILE_BYTES;
     if (it + 1 < ntiles) {
       const char* Kn = smem + ((it + 1) & 1) * 2 * TILE_BYTES;
-      tile_dma(kg, kv_rowbytes, k0 + BN, p.s_k - 1, tl, Kn, wave);
-      tile_dma(vg, kv_rowbytes, k0 + BN, p.s_k - 1, tl, Kn + TILE_BYTES, wave);
+      tile_dma(kg, kv_rowbytes, k0 + BN, p.s_k - 1, tl, Kn, wave, lane);
+      tile_dma(vg, kv_rowbytes, k0 + BN, p.s_k - 1, tl, Kn + TILE_BYTES, wave, lane);
     }
 
     const bool active = !(p.causal && k0 > q0w + 31);

@@ -58,7 +58,7 @@ __global__ void __launch_bounds__(NTHREADS, 2) k_fwd_bf16(FwdParams p) {
   const char* kg = reinterpret_cast<const char*>(p.k + kh * p.kv_sh);
   const char* vg = reinterpret_cast<const char*>(p.v + kh * p.kv_sh);
   const uint32_t kv_rowbytes = static_cast<uint32_t>(p.kv_ss) * 2;
-  const TileLane tl = tile_lane(wave, lane);
+  const TileLane tl = tile_lane(wave, lane, kv_rowbytes);
 
   // Q^T operand: lane holds Q[qrow][16 ks + 8 hh .. +7]
   bf16x8 qreg[8];
@@ -110,8 +110,8 @@ __global__ void __launch_bounds__(NTHREADS, 2) k_fwd_bf16(FwdParams p) {
 
   // K/V tiles go from global memory straight into LDS; key rows past s_k are clamped to the last
   // row and masked below.  Tile t + 1 is on its way while tile t is computed on.
-  tile_dma(kg, kv_rowbytes, 0, p.s_k - 1, tl, smem, wave);
-  tile_dma(vg, kv_rowbytes, 0, p.s_k - 1, tl, smem + TILE_BYTES, wave);
+  tile_dma(kg, kv_rowbytes, 0, p.s_k - 1, tl, smem, wave, lane);
+  tile_dma(vg, kv_rowbytes, 0, p.s_k - 1, tl, smem + TILE_BYTES, wave, lane);
   lds_dma_wait();
   __syncthreads();
 
@@ -170,8 +170,8 @@ __global__ void __launch_bounds__(NTHREADS, 2) k_fwd_bf16(FwdParams p) {
     const char* Vs = Ks + TILE_BYTES;
     if (more) {
       const char* Kn = smem + (2 * TILE_BYTES - boff);
-      tile_dma(kg, kv_rowbytes, k0 + BN, p.s_k - 1, tl, Kn, wave);
-      tile_dma(vg, kv_rowbytes, k0 + BN, p.s_k - 1, tl, Kn + TILE_BYTES, wave);
+      tile_dma(kg, kv_rowbytes, k0 + BN, p.s_k - 1, tl, Kn, wave, lane);
+      tile_dma(vg, kv_rowbytes, k0 + BN, p.s_k - 1, tl, Kn + TILE_BYTES, wave, lane);
     }
 
     const bool active = !(p.causal && k0 > q0w + 31);

@@ -132,16 +132,25 @@ __device__ __forceinline__ bf16x8 lds_gather(const char* base, int off) {
 // The copy is issued from inline assembly, so the compiler neither sees it nor waits for it:
 // lds_dma_wait() before the barrier that publishes the tile is the caller's duty.  (Compiler-
 // tracked loads stay correct next to it: extra loads in flight only make its waits stricter.)
-struct TileLane { int row[5]; uint32_t cb[5]; };   // this lane's logical tile row and byte in the row, per piece
+// Per lane and piece: the byte offset of the lane's 16 bytes from the tile's first row, for a
+// tile that lies wholly inside the matrix (voff), and the pieces' (row, byte in row) from which
+// the clamped offsets of a tile that crosses the last row are made.
+struct TileLane { uint32_t voff[5]; };
 
-__device__ __forceinline__ TileLane tile_lane(int w, int lane) {
+__device__ __forceinline__ void tile_lane_rc(int w, int lane, int j, int& row, uint32_t& cb) {
+  const int s = (w + 4 * j) * 64 + lane;
+  row = prow(s / 17);                              // prow is its own inverse
+  const int c = s % 17;
+  cb = static_cast<uint32_t>(c < 15 ? c : 15) * 16;
+}
+
+__device__ __forceinline__ TileLane tile_lane(int w, int lane, uint32_t rowbytes) {
   TileLane m;
 #pragma unroll
   for (int j = 0; j < 5; ++j) {
-    const int s = (w + 4 * j) * 64 + lane;
-    m.row[j] = prow(s / 17);                       // prow is its own inverse
-    const int c = s % 17;
-    m.cb[j] = static_cast<uint32_t>(c < 15 ? c : 15) * 16;
+    int row; uint32_t cb;
+    tile_lane_rc(w, lane, j, row, cb);
+    m.voff[j] = static_cast<uint32_t>(row) * rowbytes + cb;
   }
   return m;
 }
@@ -157,15 +166,25 @@ __device__ __forceinline__ void lds_dma16(const char* gbase, uint32_t voff, uint
 }
 
 // Rows row0 .. row0 + 63 of a [rows, d = 128] bf16 matrix at gbase (row pitch rowbytes) into the
-// padded LDS tile at `tile`; rows past `last` are clamped to it (callers mask them).
+// padded LDS tile at `tile`; rows past `last` are clamped to it (callers mask them).  A tile
+// inside the matrix costs no vector arithmetic: the tile's position goes into the scalar base.
 __device__ __forceinline__ void tile_dma(const char* gbase, uint32_t rowbytes, int row0, int last,
-                                         const TileLane& m, const char* tile, int w) {
+                                         const TileLane& m, const char* tile, int w, int lane) {
   const uint32_t base = lds_addr(tile);
+  if (row0 + 63 <= last) {
+    const char* g = gbase + static_cast<uint64_t>(static_cast<uint32_t>(row0)) * rowbytes;
 #pragma unroll
-  for (int j = 0; j < 5; ++j) {
-    if (j < 4 || w == 0) {
-      const int r = row0 + m.row[j];
-      lds_dma16(gbase, static_cast<uint32_t>(r < last ? r : last) * rowbytes + m.cb[j], base + (w + 4 * j) * 1024);
+    for (int j = 0; j < 5; ++j)
+      if (j < 4 || w == 0) lds_dma16(g, m.voff[j], base + (w + 4 * j) * 1024);
+  } else {
+#pragma unroll
+    for (int j = 0; j < 5; ++j) {
+      if (j < 4 || w == 0) {
+        int row; uint32_t cb;
+        tile_lane_rc(w, lane, j, row, cb);
+        const int r = row0 + row;
+        lds_dma16(gbase, static_cast<uint32_t>(r < last ? r : last) * rowbytes + cb, base + (w + 4 * j) * 1024);
+      }
     }
   }
 }
