@@ -102,6 +102,34 @@ def test_pair_bf16(shape):
     _run_pair(torch.bfloat16, *shape)
 
 
+@pytest.mark.parametrize("dtype,d", [(torch.bfloat16, 128), (torch.float32, 64)])
+def test_pair_token_major_layout(dtype, d):
+    """Operands laid out [tokens, heads, d] (sequence stride = heads * d, head stride = d) and seen as
+    [heads, tokens, d] views: every stride in the shape descriptor differs from the packed case."""
+    h_q, h_kv, s_q, s_k, causal = 4, 2, 200, 200, True
+    q, k, v, do = case(4242, h_q, h_kv, s_q, s_k, d, dtype)
+    scale = 1 / math.sqrt(d)
+
+    def tm(t):        # same values, token-major storage
+        return t.permute(1, 0, 2).contiguous().to(dev()).permute(1, 0, 2)
+
+    Q, K, V, dO = tm(q), tm(k), tm(v), tm(do)
+    assert Q.stride() == (d, h_q * d, 1)
+    o = torch.empty(s_q, h_q, d, device=dev()).permute(1, 0, 2)
+    lse = torch.empty(h_q, s_q, device=dev())
+    dfa.dfa_chunk_fwd(Q, K, V, causal, scale, o=o, lse=lse)
+    delta = dfa.dfa_delta(o, dO)
+    dq = torch.zeros(s_q, h_q, d, device=dev()).permute(1, 0, 2)
+    dk = torch.zeros(s_k, h_kv, d, device=dev()).permute(1, 0, 2)
+    dv = torch.zeros(s_k, h_kv, d, device=dev()).permute(1, 0, 2)
+    dfa.dfa_chunk_bwd(Q, K, V, lse, delta, dO, dq, dk, dv, causal, scale, accumulate=False)
+    torch.cuda.synchronize()
+    O, L, rq, rk, rv = _single_pair_oracle(q, k, v, do, scale, causal)
+    tol = TOL[dtype]
+    errs = dict(o=maxerr(o, O), lse=maxerr(lse, L), dq=maxerr(dq, rq), dk=maxerr(dk, rk), dv=maxerr(dv, rv))
+    assert all(e <= tol for e in errs.values()), errs
+
+
 def test_pair_bf16_output_dtype_bf16():
     _run_pair(torch.bfloat16, 2, 2, 256, 256, 128, True, o_dtype=torch.bfloat16)
 
