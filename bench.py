@@ -160,6 +160,14 @@ def main():
             timed("k_bwd_dq_bf16", record, 2.0 * w.d * w.h_q * n,
                   lambda: B.dfa_chunk_bwd(*common, chunk(bufs.dQ, qc), None, None, diag, w.scale, accumulate=acc_q))
 
+    if args.calibrate_copy:
+        src = torch.zeros(1 << 28, dtype=torch.float32, device=dev)
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        torch.add(src, 1.0, out=dst)     # one dispatch: 2^30 B read, 2^30 B written
+        torch.cuda.synchronize()
+        del src, dst
+
     for _ in range(args.warmup):
         step(False)
     torch.cuda.synchronize()
