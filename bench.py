@@ -37,6 +37,9 @@ def parse():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--config", type=int, default=1, help="index into dfa_inputs.CONFIGS (1 = the metric's workload)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--schedule", choices=("balanced", "ring"), default="balanced",
+                    help="balanced: the load-balanced schedule (the metric's workload); ring: the plain ring "
+                         "schedule, where worker P-1 computes all P of its pairs itself (ablation)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also launch one plain elementwise kernel that reads 1 GiB and writes 1 GiB, "
                          "the known-size reference for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE readings")
@@ -61,7 +64,7 @@ def traffic_from_profiles(name):
     return None
 
 
-def cpu_baseline(w, worker, heads, q, k, v, do):
+def cpu_baseline(w, worker, heads, q, k, v, do, mode="balanced"):
     """Times the fp64 oracle (as it stands) on `heads` heads of the worker's share: pair
     forward + pair backward of its five pairs.  Returns the cpu_baseline JSON object."""
     import numpy as np
@@ -84,7 +87,7 @@ def cpu_baseline(w, worker, heads, q, k, v, do):
     Lfull = np.zeros((heads, w.n_total)); Dfull = np.zeros((heads, w.n_total))
     Lfull[:, rows] = L; Dfull[:, rows] = A.delta_rows(O, do64[:, rows])
     import paper_2310_03294_amd as dfa
-    pairs = share_pairs(dfa.dfa_schedule(w.p, worker))
+    pairs = share_pairs(dfa.dfa_schedule(w.p, worker, mode))
     t0 = time.perf_counter()
     for (qc, kc, _kind) in pairs:
         A.pair_fwd(q64, k64, v64, w.scale, qc, kc, c)
@@ -117,8 +120,8 @@ def main():
     q, k, v, do = (dfa_inputs.full_sequence(w, t) for t in range(4))
     Q, K, V, dO = (t.to(dev) for t in (q, k, v, do))
     bufs = driver.Buffers(w.h_q, w.h_kv, w.n_total, w.d, w.p, dev)
-    remote = driver.helper_partials_for(Q, K, V, w.scale, w.p, worker, bufs)
-    sched = dfa.dfa_schedule(w.p, worker)
+    remote = driver.helper_partials_for(Q, K, V, w.scale, w.p, worker, bufs) if args.schedule == "balanced" else {}
+    sched = dfa.dfa_schedule(w.p, worker, args.schedule)
     pairs = share_pairs(sched)
     nnz = sum(c * (c + 1) // 2 if qc == kc else c * c for qc, kc, _ in pairs)
     flops_step = 14.0 * w.d * w.h_q * nnz
@@ -142,7 +145,8 @@ def main():
 
     def step(record):
         timed("forward", record, fwd_flops,
-              lambda: driver.forward_worker(Q, K, V, w.scale, w.p, worker, bufs, remote=remote))
+              lambda: driver.forward_worker(Q, K, V, w.scale, w.p, worker, bufs, remote=remote or None,
+                                            mode=args.schedule))
         B.dfa_delta(chunk(bufs.O, worker), chunk(dO, worker), delta=chunk(bufs.delta, worker))
         seen_q, seen_kv = set(), set()     # first contribution to a gradient chunk overwrites, the rest accumulate
         for (qc, kc, kind) in pairs:
@@ -209,7 +213,7 @@ def main():
         "value": round(tflops, 2), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": round(ms, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16" if w.dtype == "bf16" else "f32", "data": "synthetic",
-        "config": {"workload": f"{w.name}: worker {worker} share, {len(pairs)} pairs fwd+bwd + "
+        "config": {"workload": f"{w.name}: worker {worker} share ({args.schedule} schedule), {len(pairs)} pairs fwd+bwd + "
                                f"{len(remote)} remote merges, H={w.h_q}/{w.h_kv} d={w.d} C={c}",
                    "n_total": w.n_total, "P": w.p, "chunk": c},
         "pct_of_bf16_peak": round(100.0 * tflops / PEAK_BF16_TFLOPS, 2),
@@ -217,7 +221,7 @@ def main():
         "roofline": roofline,
     }
     if not args.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_baseline(w, worker, args.cpu_heads, q, k, v, do)
+        out["cpu_baseline"] = cpu_baseline(w, worker, args.cpu_heads, q, k, v, do, args.schedule)
     print(json.dumps(out), flush=True)
 
 
