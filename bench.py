@@ -37,6 +37,9 @@ def parse():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--config", type=int, default=1, help="index into dfa_inputs.CONFIGS (1 = the metric's workload)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--overlap-copy", action="store_true",
+                    help="stage the key/value chunk of each OWN forward pair one step ahead with a device-to-device "
+                         "copy on a second stream (emulates the communication overlap; forward only)")
     ap.add_argument("--schedule", choices=("balanced", "ring"), default="balanced",
                     help="balanced: the load-balanced schedule (the metric's workload); ring: the plain ring "
                          "schedule, where worker P-1 computes all P of its pairs itself (ablation)")
@@ -142,11 +145,12 @@ def main():
         ev[name].append((e0, e1, flops))
 
     fwd_flops = 4.0 * w.d * w.h_q * nnz
+    prefetch = driver.KVPrefetcher(K, V, c) if args.overlap_copy else None
 
     def step(record):
         timed("forward", record, fwd_flops,
               lambda: driver.forward_worker(Q, K, V, w.scale, w.p, worker, bufs, remote=remote or None,
-                                            mode=args.schedule))
+                                            mode=args.schedule, prefetch=prefetch))
         B.dfa_delta(chunk(bufs.O, worker), chunk(dO, worker), delta=chunk(bufs.delta, worker))
         seen_q, seen_kv = set(), set()     # first contribution to a gradient chunk overwrites, the rest accumulate
         for (qc, kc, kind) in pairs:

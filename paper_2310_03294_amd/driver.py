@@ -33,19 +33,66 @@ def _chunk(t, i, c):
     return t[:, i * c:(i + 1) * c]
 
 
-def forward_worker(Q, K, V, scale, P, w, bufs: Buffers, remote=None, mode="balanced", fused=True):
+class KVPrefetcher:
+    """Emulates the overlap of Section 3.2 (Eq. 3) on one GPU: the key/value chunk a worker needs at
+    step t + 1 is copied into a staging buffer on a second stream while step t computes.  The
+    device-to-device copy stands in for the fetch from the peer that owns the chunk; the kernels of
+    OWN pairs then read the staged copy, so the dependency (copy before use, use before the buffer is
+    overwritten) is the real one.  Both streams have the default priority."""
+
+    def __init__(self, K, V, c):
+        self.K, self.V, self.c = K, V, c
+        self.stream = torch.cuda.Stream()
+        self.buf = [(torch.empty_like(K[:, :c]), torch.empty_like(V[:, :c])) for _ in range(2)]
+        self.ev = [torch.cuda.Event(), torch.cuda.Event()]
+        self.n = 0
+
+    def fetch(self, kv_chunk):
+        """Start copying chunk `kv_chunk` into the next staging slot; returns the slot."""
+        slot = self.n & 1
+        self.n += 1
+        # the slot's previous readers (kernels already queued on the compute stream) come first
+        self.stream.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(self.stream):
+            self.buf[slot][0].copy_(_chunk(self.K, kv_chunk, self.c), non_blocking=True)
+            self.buf[slot][1].copy_(_chunk(self.V, kv_chunk, self.c), non_blocking=True)
+            self.ev[slot].record()
+        return slot
+
+    def get(self, slot):
+        torch.cuda.current_stream().wait_event(self.ev[slot])
+        return self.buf[slot]
+
+
+def _own_steps(sched):
+    return [st for st in sched if st.kind == B.DFA_STEP_OWN]
+
+
+def forward_worker(Q, K, V, scale, P, w, bufs: Buffers, remote=None, mode="balanced", fused=True, prefetch=None):
     """Forward share of worker w: its diagonal chunk, its OWN pairs folded into (O_w, L_w),
     the partials that arrive from helpers (`remote`: {helper_id: (o, lse)}) merged at the step
     they arrive, and its HELP pairs computed into fresh partial buffers.
     fused: OWN pairs continue from the state in (O_w, L_w) (dfa_chunk_fwd_acc, the attn(q, k, v,
     o, s) call of Algorithms 1-2); otherwise each is a partial result plus a dfa_merge.
+    prefetch: a KVPrefetcher; the key/value chunk of every OWN pair is then staged one step ahead
+    on a second stream (fused path only).
     Returns {owner_id: (o_part, lse_part)} for the HELP pairs this worker computed."""
     c = bufs.c
     sent = {}
     o_w, l_w = _chunk(bufs.O, w, c), _chunk(bufs.L, w, c)
-    for st in B.dfa_schedule(P, w, mode):
+    sched = B.dfa_schedule(P, w, mode)
+    own = _own_steps(sched) if prefetch is not None else []
+    nxt, slot = 0, None
+    for st in sched:
         if st.kind == B.DFA_STEP_DIAG:
+            if own:
+                slot = prefetch.fetch(own[0].kv_chunk); nxt = 1      # copy for step 1 runs under the diagonal pair
             B.dfa_chunk_fwd(_chunk(Q, w, c), _chunk(K, w, c), _chunk(V, w, c), True, scale, o=o_w, lse=l_w)
+        elif st.kind == B.DFA_STEP_OWN and fused and prefetch is not None:
+            k_s, v_s = prefetch.get(slot)
+            if nxt < len(own):
+                slot = prefetch.fetch(own[nxt].kv_chunk); nxt += 1   # copy for the next step runs under this pair
+            B.dfa_chunk_fwd_acc(_chunk(Q, w, c), k_s, v_s, False, scale, o_w, l_w)
         elif st.kind == B.DFA_STEP_OWN and fused:
             B.dfa_chunk_fwd_acc(_chunk(Q, w, c), _chunk(K, st.kv_chunk, c), _chunk(V, st.kv_chunk, c), False, scale,
                                 o_w, l_w)

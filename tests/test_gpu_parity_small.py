@@ -271,3 +271,22 @@ def test_chunk_fwd_acc_chain(dtype, d, o_dtype):
     assert maxerr(o, O) <= tol and maxerr(lse, L) <= (1e-5 if dtype == torch.float32 else 2e-2)
     assert maxerr(o, np64(o_m)) <= (2e-5 if (dtype == torch.float32) else 2e-2)
     assert maxerr(lse, np64(l_m)) <= 1e-5
+
+
+def test_forward_with_staged_kv_equals_direct():
+    """OWN pairs reading key/value chunks staged one step ahead on a second stream (the overlap of
+    Section 3.2 emulated with a device-to-device copy) give bit-identical results, run after run."""
+    w = dfa_inputs.Workload("t_prefetch", 4, 2, 128, 256 * 8, 8, "bf16", 777)
+    q, k, v, _ = (dfa_inputs.full_sequence(w, t) for t in range(4))
+    Q, K, V = (t.to(dev()) for t in (q, k, v))
+    worker = w.p - 1
+    ref = driver.Buffers(w.h_q, w.h_kv, w.n_total, w.d, w.p, dev(), grads=False)
+    driver.forward_worker(Q, K, V, w.scale, w.p, worker, ref, mode="ring")
+    pf = driver.KVPrefetcher(K, V, w.chunk)
+    c = w.chunk
+    for _ in range(3):
+        got = driver.Buffers(w.h_q, w.h_kv, w.n_total, w.d, w.p, dev(), grads=False)
+        driver.forward_worker(Q, K, V, w.scale, w.p, worker, got, mode="ring", prefetch=pf)
+        torch.cuda.synchronize()
+        assert torch.equal(got.O[:, worker * c:], ref.O[:, worker * c:])
+        assert torch.equal(got.L[:, worker * c:], ref.L[:, worker * c:])
