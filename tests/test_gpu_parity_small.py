@@ -290,3 +290,44 @@ def test_forward_with_staged_kv_equals_direct():
         torch.cuda.synchronize()
         assert torch.equal(got.O[:, worker * c:], ref.O[:, worker * c:])
         assert torch.equal(got.L[:, worker * c:], ref.L[:, worker * c:])
+
+
+@pytest.mark.parametrize("causal", [False, True])
+def test_forward_running_maximum_moves(causal):
+    """Scores that grow along the key axis by far more than the lazy-maximum threshold (2^8 in the
+    exp2 domain per step): every tile moves the reference and rescales O and the row sum; the
+    backward sees probabilities spanning the whole exponent range."""
+    h, s, d = 2, 1024, 128
+    g = torch.Generator().manual_seed(5)
+    q = torch.randn(h, s, d, generator=g)
+    k = torch.randn(h, s, d, generator=g) * 0.3
+    # add to every key a component along each query's mean direction, growing with the key index
+    u = q.mean(1, keepdim=True); u = u / u.norm(dim=-1, keepdim=True)
+    ramp = torch.linspace(0.0, 60.0, s).view(1, s, 1)
+    k = k + ramp * u
+    q = q + 4.0 * u                      # q.u ~ 4 -> scaled scores ramp up to ~ 60 * 4 / sqrt(128) = 21 (2^30)
+    v = torch.randn(h, s, d, generator=g)
+    do = torch.randn(h, s, d, generator=g)
+    q, k, v, do = (t.to(torch.bfloat16) for t in (q, k, v, do))
+    scale = 1 / math.sqrt(d)
+    Q, K, V, dO = (t.to(dev()) for t in (q, k, v, do))
+    o, lse = dfa.dfa_chunk_fwd(Q, K, V, causal, scale)
+    # the same through two halves of the keys with the state carried over
+    if not causal:
+        o2 = torch.zeros_like(o); l2 = torch.full_like(lse, -math.inf)
+        dfa.dfa_chunk_fwd_acc(Q, K[:, :512], V[:, :512], False, scale, o2, l2)
+        dfa.dfa_chunk_fwd_acc(Q, K[:, 512:], V[:, 512:], False, scale, o2, l2)
+    delta = dfa.dfa_delta(o, dO)
+    dq = torch.zeros(h, s, d, device=dev()); dk = torch.zeros_like(dq); dv = torch.zeros_like(dq)
+    dfa.dfa_chunk_bwd(Q, K, V, lse, delta, dO, dq, dk, dv, causal, scale)
+    torch.cuda.synchronize()
+    O, L, rq, rk, rv = _single_pair_oracle(q, k, v, do, scale, causal)
+    assert float(L.max() - L.min()) > 12.0          # the logsumexp itself spans many e-folds across rows
+    tol = TOL[torch.bfloat16]
+    errs = dict(o=maxerr(o, O), lse=maxerr(lse, L), dq=maxerr(dq, rq), dk=maxerr(dk, rk), dv=maxerr(dv, rv))
+    if not causal:
+        errs.update(o_acc=maxerr(o2, O), lse_acc=maxerr(l2, L))
+    # gradients here reach magnitudes of tens: bound them relative to their scale as well
+    scale_of = dict(o=1.0, lse=1.0, o_acc=1.0, lse_acc=1.0, dq=max(1.0, np.abs(rq).max()),
+                    dk=max(1.0, np.abs(rk).max()), dv=max(1.0, np.abs(rv).max()))
+    assert all(errs[n] <= tol * scale_of[n] for n in errs), (errs, scale_of)
