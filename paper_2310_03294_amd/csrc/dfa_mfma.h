@@ -35,54 +35,9 @@ __device__ __forceinline__ f32x16 mfma32(bf16x8 a, bf16x8 b, f32x16 c) {
   return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
 }
 
-// The same instruction with the register file of each operand fixed by hand.  gfx950 has 256
-// architectural VGPRs (the only ones VALU instructions can touch) and 256 accumulation VGPRs
-// (AGPRs) per lane at one wavefront per SIMD.  A kernel whose MFMA-only state (long-lived
-// accumulators, loop-invariant B operands) is pinned in AGPRs keeps the VGPRs free for the
-// softmax arithmetic and for LDS reads in flight.  Suffixes: accumulator file (a|v), then the
-// files of the A and B operands.  "z" forms start a chain with C = 0.  "_last" forms end a
-// chain whose result is read by VALU instructions next: the hardware does not interlock that
-// read, so they carry the wait states themselves (16 cover the 8-pass 32x32x16 MFMA).
-__device__ __forceinline__ void mfma_a_vv(f32x16& acc, bf16x8 a, bf16x8 b) {
-  asm("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+a"(acc) : "v"(a), "v"(b));
-}
-__device__ __forceinline__ void mfma_vz_va(f32x16& acc, bf16x8 a, bf16x8 b) {
-  asm("v_mfma_f32_32x32x16_bf16 %0, %1, %2, 0" : "=&v"(acc) : "v"(a), "a"(b));
-}
-__device__ __forceinline__ void mfma_v_va(f32x16& acc, bf16x8 a, bf16x8 b) {
-  asm("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(acc) : "v"(a), "a"(b));
-}
-__device__ __forceinline__ void mfma_v_va_last(f32x16& acc, bf16x8 a, bf16x8 b) {
-  asm("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0\n\ts_nop 15" : "+v"(acc) : "v"(a), "a"(b));
-}
-// Last step of two chains at once (the compiler may reorder independent asm statements, so
-// the wait states have to sit in the same statement as BOTH final MFMAs).
-__device__ __forceinline__ void mfma2_v_va_last(f32x16& acc0, bf16x8 a0, bf16x8 b0,
-                                                f32x16& acc1, bf16x8 a1, bf16x8 b1) {
-  asm("v_mfma_f32_32x32x16_bf16 %0, %2, %3, %0\n\tv_mfma_f32_32x32x16_bf16 %1, %4, %5, %1\n\ts_nop 15"
-      : "+v"(acc0), "+v"(acc1) : "v"(a0), "a"(b0), "v"(a1), "a"(b1));
-}
-__device__ __forceinline__ void mfma_vz_vv(f32x16& acc, bf16x8 a, bf16x8 b) {
-  asm("v_mfma_f32_32x32x16_bf16 %0, %1, %2, 0" : "=&v"(acc) : "v"(a), "v"(b));
-}
-__device__ __forceinline__ void mfma_v_vv(f32x16& acc, bf16x8 a, bf16x8 b) {
-  asm("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(acc) : "v"(a), "v"(b));
-}
-__device__ __forceinline__ void mfma_v_vv_last(f32x16& acc, bf16x8 a, bf16x8 b) {
-  asm("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0\n\ts_nop 15" : "+v"(acc) : "v"(a), "v"(b));
-}
-
-// Moves a loop-invariant MFMA operand into AGPRs for good.
-__device__ __forceinline__ bf16x8 to_agpr(bf16x8 x) {
-  typedef int i32x4 __attribute__((ext_vector_type(4)));
-  const i32x4 v = __builtin_bit_cast(i32x4, x);
-  i32x4 r;
-  asm volatile("v_accvgpr_write_b32 %0, %1" : "=a"(r[0]) : "v"(v[0]));
-  asm volatile("v_accvgpr_write_b32 %0, %1" : "=a"(r[1]) : "v"(v[1]));
-  asm volatile("v_accvgpr_write_b32 %0, %1" : "=a"(r[2]) : "v"(v[2]));
-  asm volatile("v_accvgpr_write_b32 %0, %1" : "=a"(r[3]) : "v"(v[3]));
-  return __builtin_bit_cast(bf16x8, r);
-}
+// (Inline-assembly forms of the MFMA with operand register files fixed by hand were tried and
+// dropped: hipcc places accumulator copies next to such statements without the wait states the
+// hardware needs there, which gave wrong results; the builtin above is the only form used.)
 
 #define DFA_SCHED_FENCE() __builtin_amdgcn_sched_barrier(0)
 
