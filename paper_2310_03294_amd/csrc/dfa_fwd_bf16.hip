@@ -278,6 +278,267 @@ __global__ void __launch_bounds__(NTHREADS, 2) k_fwd_bf16(FwdParams p) {
   }
 }
 
+// ============================================================================================
+// Wavefront-specialised forward for full (unmasked) pairs: 16 wavefronts on 256 query rows, four
+// per SIMD.
+//   8 "S" wavefronts (32 query rows each, Q^T in registers): S^T = K Q^T, online softmax (one
+//     reference update per 64-key tile), and the exponentiated tile P^T handed over through LDS as
+//     bf16 together with the factor by which the running maximum moved; wavefronts 0-3 also issue
+//     the global -> LDS copies of the K tiles, 4-7 those of the V tiles;
+//   8 "PV" wavefronts (the same 32 rows each): O^T = O^T * factor + V^T P^T, one tile behind their
+//     S wavefront, so one barrier per tile suffices; with only O^T to hold they read V^T six steps
+//     ahead of their MFMAs.
+// A wavefront overlaps nothing with itself (measured), different wavefronts of a SIMD do: here the
+// exponentials of two S wavefronts run under the MFMAs of all four.  Measured against the
+// 4-wavefront kernel above: 10 % faster on a 4096 x 4096 pair in spite of a lower clock under
+// load (1.8 GHz); 5 % slower on the causal diagonal pair (256-row granularity), which therefore
+// stays with the kernel above.
+// ============================================================================================
+namespace r16 {
+
+constexpr int NT = 1024;
+constexpr int BMW = 256;                       // query rows per workgroup
+constexpr int PX_BYTES = 8 * 4096;             // P^T hand-over: 8 query blocks x (64 keys x 32 queries bf16)
+constexpr int AL_BYTES = 8 * 32 * 4;           // rescale factor per query row
+// LDS map.  Tile t: K slot t % 2, V slot t % 3, P^T / factor slot t % 2; row statistics at the end.
+constexpr int OFF_K = 0;
+constexpr int OFF_V = OFF_K + 2 * TILE_BYTES;
+constexpr int OFF_PX = OFF_V + 3 * TILE_BYTES;
+constexpr int OFF_AL = OFF_PX + 2 * PX_BYTES;
+constexpr int OFF_ST = OFF_AL + 2 * AL_BYTES;  // 1 / row sum, written once by the S wavefronts
+constexpr int SMEM_BYTES = OFF_ST + AL_BYTES;
+
+__global__ void __launch_bounds__(NT, 1) k_fwd_bf16(FwdParams p) {
+  extern __shared__ __align__(16) char smem[];
+
+  const int bid = blockIdx.x;
+  const int item = (bid & 7) * p.per_xcd + (bid >> 3);   // contiguous (head, query tile) range per XCD
+  if (item >= p.total) return;
+  const int head = item / p.ntq;
+  int tq = item % p.ntq;
+  if (p.causal) tq = p.ntq - 1 - tq;      // longest rows first
+  const int kh = head / p.group;
+  const int q0 = tq * BMW;
+
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform: role branches stay scalar
+  const bool pv_wave = wave >= 8;
+  const int r32 = lane & 31, hh = lane >> 5;
+  const float c2 = p.scale * LOG2E;
+
+  const int k_end = p.causal ? min(p.s_k, q0 + BMW) : p.s_k;
+  const int ntiles = (k_end + BN - 1) / BN;
+
+  if (!pv_wave) {
+    // ------------------------------------------------------------------ S wavefront
+    const int q0w = q0 + wave * 32;
+    const int qrow = q0w + r32;
+    const bool qvalid = qrow < p.s_q;
+    const int a_base = tile_off(r32, hh);
+    bf16x8 qreg[8];      // Q^T operand: lane holds Q[qrow][16 ks + 8 hh .. +7]
+    {
+      const __bf16* qp = p.q + head * p.q_sh + static_cast<int64_t>(qvalid ? qrow : 0) * p.q_ss + 8 * hh;
+#pragma unroll
+      for (int ks = 0; ks < 8; ++ks) {
+        uint4 raw = *reinterpret_cast<const uint4*>(qp + 16 * ks);
+        if (!qvalid) raw = make_uint4(0, 0, 0, 0);
+        qreg[ks] = __builtin_bit_cast(bf16x8, raw);
+      }
+    }
+    float m_run = -INFINITY;     // running maximum of the raw scores q.k
+    float l_run = 0.f;           // this lane's half of the running row sum
+    if (p.accumulate && qvalid) {
+      // state of the earlier key/value chunks: running (o, m, l) with m = lse (raw-score units), l = 1
+      const float L = p.lse[head * p.l_sh + qrow];
+      if (L > -INFINITY) { m_run = L / p.scale; l_run = hh == 0 ? 1.f : 0.f; }
+    }
+    float* al = reinterpret_cast<float*>(smem + OFF_AL) + wave * 32 + r32;
+    // the S wavefronts (registers to spare) issue the global -> LDS copies of the K/V tiles
+    const char* kg = reinterpret_cast<const char*>(p.k + kh * p.kv_sh);
+    const char* vg = reinterpret_cast<const char*>(p.v + kh * p.kv_sh);
+    const uint32_t kv_rowbytes = static_cast<uint32_t>(p.kv_ss) * 2;
+    const TileLane tl = tile_lane(wave & 3, lane, kv_rowbytes);
+    const char* cg = wave < 4 ? kg : vg;      // wavefronts 0-3 copy K tiles, 4-7 V tiles
+    const int last = p.s_k - 1;
+    tile_dma(cg, kv_rowbytes, 0, last, tl, wave < 4 ? smem + OFF_K : smem + OFF_V, wave & 3, lane);
+    lds_dma_wait();
+    __syncthreads();                         // tile 0 is in LDS
+    for (int it = 0; it < ntiles; ++it) {
+      const int k0 = it * BN;
+      const char* Ks = smem + OFF_K + (it & 1) * TILE_BYTES;
+      if (it + 1 < ntiles) {
+        tile_dma(cg, kv_rowbytes, k0 + BN, last, tl,
+                 wave < 4 ? smem + OFF_K + ((it + 1) & 1) * TILE_BYTES : smem + OFF_V + ((it + 1) % 3) * TILE_BYTES,
+                 wave & 3, lane);
+      }
+      if (!(p.causal && k0 > q0w + 31)) {    // else: the whole tile lies above this block's diagonal
+        f32x16 s0, s1;
+        {
+          bf16x8 x0[4], x1[4];
+          f32x16 zero;
+#pragma unroll
+          for (int j = 0; j < 16; ++j) zero[j] = 0.f;
+#pragma unroll
+          for (int ks = 0; ks < 3; ++ks) {
+            x0[ks] = lds_read_b128(Ks, a_base + ks * 32);
+            x1[ks] = lds_read_b128(Ks, a_base + 32 * kRowBytes + ks * 32);
+          }
+          DFA_SCHED_FENCE();
+#pragma unroll
+          for (int ks = 0; ks < 8; ++ks) {
+            if (ks + 3 < 8) {
+              x0[(ks + 3) & 3] = lds_read_b128(Ks, a_base + (ks + 3) * 32);
+              x1[(ks + 3) & 3] = lds_read_b128(Ks, a_base + 32 * kRowBytes + (ks + 3) * 32);
+            }
+            s0 = mfma32(x0[ks & 3], qreg[ks], ks == 0 ? zero : s0);
+            s1 = mfma32(x1[ks & 3], qreg[ks], ks == 0 ? zero : s1);
+            DFA_SCHED_FENCE();
+          }
+        }
+        if ((k0 + BN > p.s_k) || (p.causal && k0 + BN - 1 > q0w)) {
+#pragma unroll
+          for (int j = 0; j < 16; ++j) {
+            const int kvi = k0 + (j >> 2) * 8 + hh * 4 + (j & 3);
+            if (kvi >= p.s_k || (p.causal && kvi > qrow)) s0[j] = -INFINITY;
+            if (kvi + 32 >= p.s_k || (p.causal && kvi + 32 > qrow)) s1[j] = -INFINITY;
+          }
+        }
+        // Online softmax of the 64-key tile (exp2 domain) with a lazy running maximum: the
+        // reference only moves when some row's tile maximum exceeds it by more than 2^8 (or on
+        // the first tile); until then exponentials against the stale maximum stay below 2^8 and
+        // O needs no rescaling.  The final division by the row sum removes the reference.
+        float mx = fmaxf(s0[0], s1[0]);
+#pragma unroll
+        for (int j = 1; j < 16; ++j) mx = fmaxf(fmaxf(mx, s0[j]), s1[j]);
+        float alpha = 1.f;
+        if (__any((mx - m_run) * c2 > 8.f)) {          // -inf reference (first tile) also lands here
+          mx = fmaxf(mx, __shfl_xor(mx, 32));
+          const float m_new = fmaxf(m_run, mx);
+          const float mc_new = (m_new == -INFINITY) ? 0.f : m_new * c2;
+          alpha = __builtin_amdgcn_exp2f(m_run * c2 - mc_new);
+          m_run = m_new;
+          l_run *= alpha;
+        }
+        const float mc = (m_run == -INFINITY) ? 0.f : m_run * c2;
+        float sum = 0.f;
+#pragma unroll
+        for (int j = 0; j < 16; ++j) {
+          s0[j] = __builtin_amdgcn_exp2f(fmaf(s0[j], c2, -mc));
+          s1[j] = __builtin_amdgcn_exp2f(fmaf(s1[j], c2, -mc));
+          sum += s0[j] + s1[j];
+        }
+        l_run += sum;
+        // hand P^T and the factor to the PV wavefront: lane-private, any layout will do
+        char* px = smem + OFF_PX + (it & 1) * PX_BYTES + wave * 4096 + lane * 16;
+        *reinterpret_cast<bf16x8*>(px) = pack8(s0, 0);
+        *reinterpret_cast<bf16x8*>(px + 1024) = pack8(s0, 8);
+        *reinterpret_cast<bf16x8*>(px + 2048) = pack8(s1, 0);
+        *reinterpret_cast<bf16x8*>(px + 3072) = pack8(s1, 8);
+        if (hh == 0) al[(it & 1) * (AL_BYTES / 4)] = alpha;
+      }
+      lds_dma_wait();
+      __syncthreads();
+    }
+    // row statistics: logsumexp to memory, 1 / row sum to the PV wavefront
+    const float l_tot = l_run + __shfl_xor(l_run, 32);
+    if (hh == 0) {
+      reinterpret_cast<float*>(smem + OFF_ST)[wave * 32 + r32] = l_tot > 0.f ? 1.f / l_tot : 0.f;
+      if (qvalid) p.lse[head * p.l_sh + qrow] = l_tot > 0.f ? m_run * p.scale + logf(l_tot) : -INFINITY;
+    }
+    __syncthreads();                         // the PV wavefronts' last slot
+  } else {
+    // ------------------------------------------------------------------ PV wavefront
+    const int sw = wave - 8;                 // serves S wavefront sw: the same 32 query rows
+    const int q0w = q0 + sw * 32;
+    const int qrow = q0w + r32;
+    const bool qvalid = qrow < p.s_q;
+    const int g_base = gather_base(lane);
+
+    f32x16 o[4];         // O^T: [d block][d within block][query]
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+      for (int j = 0; j < 16; ++j) o[i][j] = 0.f;
+    if (p.accumulate && qvalid && p.lse[head * p.l_sh + qrow] > -INFINITY) {
+      const int64_t obase = head * p.o_sh + static_cast<int64_t>(qrow) * p.o_ss;
+#pragma unroll
+      for (int db = 0; db < 4; ++db)
+#pragma unroll
+        for (int g4 = 0; g4 < 4; ++g4) {
+          const int col = db * 32 + g4 * 8 + hh * 4;
+          if (p.o_bf16) {
+            const bf16x4 x = *reinterpret_cast<const bf16x4*>(static_cast<const __bf16*>(p.o) + obase + col);
+#pragma unroll
+            for (int e = 0; e < 4; ++e) o[db][g4 * 4 + e] = static_cast<float>(x[e]);
+          } else {
+            const float4 x = *reinterpret_cast<const float4*>(static_cast<const float*>(p.o) + obase + col);
+            o[db][g4 * 4] = x.x; o[db][g4 * 4 + 1] = x.y; o[db][g4 * 4 + 2] = x.z; o[db][g4 * 4 + 3] = x.w;
+          }
+        }
+    }
+    // O^T = O^T * factor + V^T P^T for tile t (skipped when the tile lies above the block's diagonal)
+    auto pv_tile = [&](int t) {
+      const int k0 = t * BN;
+      if (p.causal && k0 > q0w + 31) return;
+      const char* Vs = smem + OFF_V + (t % 3) * TILE_BYTES;
+      const char* px = smem + OFF_PX + (t & 1) * PX_BYTES + sw * 4096 + lane * 16;
+      const float a = reinterpret_cast<const float*>(smem + OFF_AL)[(t & 1) * (AL_BYTES / 4) + sw * 32 + r32];
+      constexpr int AHEAD = 6;               // V^T gathers run this many steps ahead of their MFMAs
+      auto voff = [&](int n) {               // n = key block * 8 + half * 4 + d block
+        return g_base + ((n >> 3) * 32 + ((n >> 2) & 1) * 16) * kRowBytes + (n & 3) * 64;
+      };
+      bf16x8 y[AHEAD + 1], pa[4];
+#pragma unroll
+      for (int j = 0; j < 4; ++j) pa[j] = *reinterpret_cast<const bf16x8*>(px + j * 1024);
+#pragma unroll
+      for (int n = 0; n < AHEAD; ++n) y[n] = lds_gather(Vs, voff(n));
+      if (__any(a != 1.f)) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+#pragma unroll
+          for (int j = 0; j < 16; ++j) o[i][j] *= a;
+      }
+      DFA_SCHED_FENCE();
+#pragma unroll
+      for (int n = 0; n < 16; ++n) {
+        if (n + AHEAD < 16) y[(n + AHEAD) % (AHEAD + 1)] = lds_gather(Vs, voff(n + AHEAD));
+        o[n & 3] = mfma32(y[n % (AHEAD + 1)], pa[n >> 2], o[n & 3]);
+        DFA_SCHED_FENCE();
+      }
+    };
+
+    __syncthreads();                         // tile 0 is in LDS
+    for (int it = 0; it < ntiles; ++it) {    // slot it: finish tile it - 1
+      if (it > 0) pv_tile(it - 1);
+      __syncthreads();
+    }
+    pv_tile(ntiles - 1);
+    __syncthreads();                         // row statistics are in LDS
+
+    if (qvalid) {
+      const float inv = reinterpret_cast<const float*>(smem + OFF_ST)[sw * 32 + r32];
+      const int64_t obase = head * p.o_sh + static_cast<int64_t>(qrow) * p.o_ss;
+#pragma unroll
+      for (int db = 0; db < 4; ++db)
+#pragma unroll
+        for (int g4 = 0; g4 < 4; ++g4) {
+          const int col = db * 32 + g4 * 8 + hh * 4;
+          const float x0 = o[db][g4 * 4 + 0] * inv, x1 = o[db][g4 * 4 + 1] * inv;
+          const float x2 = o[db][g4 * 4 + 2] * inv, x3 = o[db][g4 * 4 + 3] * inv;
+          if (p.o_bf16) {
+            bf16x4 x; x[0] = static_cast<__bf16>(x0); x[1] = static_cast<__bf16>(x1);
+            x[2] = static_cast<__bf16>(x2); x[3] = static_cast<__bf16>(x3);
+            *reinterpret_cast<bf16x4*>(static_cast<__bf16*>(p.o) + obase + col) = x;
+          } else {
+            *reinterpret_cast<float4*>(static_cast<float*>(p.o) + obase + col) = make_float4(x0, x1, x2, x3);
+          }
+        }
+    }
+  }
+}
+
+}  // namespace r16
+
 }  // namespace
 
 int launch_fwd_bf16(const dfa_shape& sh, const void* q, const void* k, const void* v,
@@ -289,6 +550,20 @@ int launch_fwd_bf16(const dfa_shape& sh, const void* q, const void* k, const voi
   p.o_bf16 = sh.o_dtype == DFA_BF16; p.scale = sh.scale; p.accumulate = accumulate;
   p.q_sh = sh.q_stride_h; p.q_ss = sh.q_stride_s; p.kv_sh = sh.kv_stride_h; p.kv_ss = sh.kv_stride_s;
   p.o_sh = sh.o_stride_h; p.o_ss = sh.o_stride_s; p.l_sh = sh.lse_stride_h;
+  if (!sh.causal) {   // full pairs: the wavefront-specialised kernel; the diagonal pair keeps the finer 128-row tiling
+    p.ntq = (sh.s_q + r16::BMW - 1) / r16::BMW;
+    p.total = p.ntq * sh.h_q;
+    p.per_xcd = (p.total + 7) / 8;
+    static bool attr2 = false;
+    if (!attr2) {
+      const int rc = hip_status(hipFuncSetAttribute(reinterpret_cast<const void*>(r16::k_fwd_bf16),
+                                                    hipFuncAttributeMaxDynamicSharedMemorySize, r16::SMEM_BYTES));
+      if (rc) return rc;
+      attr2 = true;
+    }
+    r16::k_fwd_bf16<<<p.per_xcd * 8, r16::NT, r16::SMEM_BYTES, st>>>(p);
+    return last_launch_status();
+  }
   p.ntq = (sh.s_q + BM - 1) / BM;
   const int64_t total = static_cast<int64_t>(p.ntq) * sh.h_q;
   if (total > (1 << 30)) return DFA_ERR_SHAPE;
