@@ -294,7 +294,7 @@ __global__ void __launch_bounds__(NTHREADS, 2) k_fwd_bf16(FwdParams p) {
 // load (1.8 GHz); 5 % slower on the causal diagonal pair (256-row granularity), which therefore
 // stays with the kernel above.
 // ============================================================================================
-namespace r16 {
+namespace full_pair {
 
 constexpr int NT = 1024;
 constexpr int BMW = 256;                       // query rows per workgroup
@@ -537,7 +537,7 @@ __global__ void __launch_bounds__(NT, 1) k_fwd_bf16(FwdParams p) {
   }
 }
 
-}  // namespace r16
+}  // namespace full_pair
 
 }  // namespace
 
@@ -551,17 +551,17 @@ int launch_fwd_bf16(const dfa_shape& sh, const void* q, const void* k, const voi
   p.q_sh = sh.q_stride_h; p.q_ss = sh.q_stride_s; p.kv_sh = sh.kv_stride_h; p.kv_ss = sh.kv_stride_s;
   p.o_sh = sh.o_stride_h; p.o_ss = sh.o_stride_s; p.l_sh = sh.lse_stride_h;
   if (!sh.causal) {   // full pairs: the wavefront-specialised kernel; the diagonal pair keeps the finer 128-row tiling
-    p.ntq = (sh.s_q + r16::BMW - 1) / r16::BMW;
+    p.ntq = (sh.s_q + full_pair::BMW - 1) / full_pair::BMW;
     p.total = p.ntq * sh.h_q;
     p.per_xcd = (p.total + 7) / 8;
     static bool attr2 = false;
     if (!attr2) {
-      const int rc = hip_status(hipFuncSetAttribute(reinterpret_cast<const void*>(r16::k_fwd_bf16),
-                                                    hipFuncAttributeMaxDynamicSharedMemorySize, r16::SMEM_BYTES));
+      const int rc = hip_status(hipFuncSetAttribute(reinterpret_cast<const void*>(full_pair::k_fwd_bf16),
+                                                    hipFuncAttributeMaxDynamicSharedMemorySize, full_pair::SMEM_BYTES));
       if (rc) return rc;
       attr2 = true;
     }
-    r16::k_fwd_bf16<<<p.per_xcd * 8, r16::NT, r16::SMEM_BYTES, st>>>(p);
+    full_pair::k_fwd_bf16<<<p.per_xcd * 8, full_pair::NT, full_pair::SMEM_BYTES, st>>>(p);
     return last_launch_status();
   }
   p.ntq = (sh.s_q + BM - 1) / BM;
