@@ -117,6 +117,56 @@ def attention_bwd(Q, K, V, dO, scale, causal=True, row_block=512):
     return dQ, dK, dV
 
 
+def _window_scores(q, k, scale, c, window_chunks):
+    """scale * q k^T over a whole head with -inf outside the chunk-level causal window: key j is
+    kept for query i iff j <= i and chunk(j) >= chunk(i) - window_chunks, chunk(x) = x // c."""
+    n = q.shape[0]
+    i = np.arange(n)[:, None]
+    j = np.arange(k.shape[0])[None, :]
+    keep = (j <= i) & (j // c >= i // c - window_chunks)
+    return np.where(keep, scale * (q @ k.T), -np.inf)
+
+
+def window_attention_fwd(Q, K, V, scale, c, window_chunks):
+    """Causal attention local to the query's own chunk of c tokens and the `window_chunks`
+    chunks before it (appendix on sparse patterns, local sliding windows, at the granularity the
+    paper describes: whole chunks of the preceding workers).  Monolithic per head; returns (O, L)."""
+    Q = np.asarray(Q, np.float64); K = np.asarray(K, np.float64); V = np.asarray(V, np.float64)
+    h_q, n, _ = Q.shape
+    h_kv = K.shape[0]
+    O = np.empty((h_q, n, V.shape[2]), np.float64)
+    L = np.empty((h_q, n), np.float64)
+    for h in range(h_q):
+        kh = _kv_head(h, h_q, h_kv)
+        s = _window_scores(Q[h], K[kh], scale, c, window_chunks)
+        m = s.max(axis=1, keepdims=True)
+        e = np.exp(s - m)
+        l = e.sum(axis=1, keepdims=True)
+        O[h] = (e / l) @ V[kh]
+        L[h] = (m + np.log(l))[:, 0]
+    return O, L
+
+
+def window_attention_bwd(Q, K, V, dO, scale, c, window_chunks):
+    """Analytic backward of window_attention_fwd (same formulas as attention_bwd)."""
+    Q = np.asarray(Q, np.float64); K = np.asarray(K, np.float64)
+    V = np.asarray(V, np.float64); dO = np.asarray(dO, np.float64)
+    h_q = Q.shape[0]
+    h_kv = K.shape[0]
+    dQ = np.zeros_like(Q); dK = np.zeros_like(K); dV = np.zeros_like(V)
+    for h in range(h_q):
+        kh = _kv_head(h, h_q, h_kv)
+        s = _window_scores(Q[h], K[kh], scale, c, window_chunks)
+        e = np.exp(s - s.max(axis=1, keepdims=True))
+        p = e / e.sum(axis=1, keepdims=True)
+        dp = dO[h] @ V[kh].T
+        ds = p * (dp - (p * dp).sum(axis=1, keepdims=True))
+        dV[kh] += p.T @ dO[h]
+        dQ[h] = scale * (ds @ K[kh])
+        dK[kh] += scale * (ds.T @ Q[h])
+    return dQ, dK, dV
+
+
 def delta_rows(O, dO):
     """D_i = sum_c dO_ic O_ic, which equals sum_j P_ij dP_ij for the exact O."""
     return (np.asarray(O, np.float64) * np.asarray(dO, np.float64)).sum(axis=-1)

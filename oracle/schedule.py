@@ -66,6 +66,15 @@ def ring_worker(P: int, p1: int):
     return steps
 
 
+def window_worker(P: int, p1: int, window_chunks: int):
+    """Steps of 1-indexed worker p1 when attention is local to the `window_chunks` preceding
+    workers (appendix on sparse patterns, "local sliding windows"): the vanilla algorithm with
+    the end of its loop moved from the first worker to the one `window_chunks` positions
+    earlier.  1 + window_chunks time steps; no helpers (the load is near balanced by itself)."""
+    assert 1 <= p1 <= P and window_chunks >= 0
+    return ring_worker(P, p1)[:1 + min(window_chunks, P - 1)]
+
+
 def balanced(P: int):
     """Step lists of all workers, 0-indexed by worker."""
     return [balanced_worker(P, p1) for p1 in range(1, P + 1)]
@@ -73,6 +82,10 @@ def balanced(P: int):
 
 def ring(P: int):
     return [ring_worker(P, p1) for p1 in range(1, P + 1)]
+
+
+def window(P: int, window_chunks: int):
+    return [window_worker(P, p1, window_chunks) for p1 in range(1, P + 1)]
 
 
 def idle_slots(sched) -> int:

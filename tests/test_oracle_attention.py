@@ -214,3 +214,81 @@ def test_row_and_column_samplers_match_full():
         a, b = A.cols_dkdv(k[kh, cols], v[kh, cols], cols, q[hh], do[hh], L[hh], D[hh], scale)
         dk_c += a; dv_c += b
     assert np.abs(dk_c - dK[kh, cols]).max() < 1e-13 and np.abs(dv_c - dV[kh, cols]).max() < 1e-13
+
+
+# ----------------------------------------------------------------- chunk-level local window
+def test_window_brute_force_and_limits():
+    """The windowed attention against pure-Python loops over the kept keys, its two limits
+    (window >= P-1: plain causal attention; window 0: every chunk on its own) and the
+    worked example of the appendix (window of one worker: worker 7 sees workers 6 and 7)."""
+    h_q, h_kv, c, P, d = 2, 1, 5, 4, 3
+    n = c * P
+    q, k, v, do = _case(41, h_q, h_kv, n, d)
+    scale = 0.41
+    for w in (0, 1, 2):
+        O, L = A.window_attention_fwd(q, k, v, scale, c, w)
+        for h in range(h_q):
+            for i in range(n):
+                keys = [j for j in range(i + 1) if j // c >= i // c - w]
+                z = [math.exp(scale * sum(q[h, i, x] * k[0, j, x] for x in range(d))) for j in keys]
+                tot = sum(z)
+                for x in range(d):
+                    ref = sum(zj * v[0, j, x] for zj, j in zip(z, keys)) / tot
+                    assert abs(O[h, i, x] - ref) < 1e-12
+                assert abs(L[h, i] - math.log(tot)) < 1e-12
+    Of, Lf = A.attention_fwd(q, k, v, scale)
+    Ow, Lw = A.window_attention_fwd(q, k, v, scale, c, P - 1)
+    assert np.abs(Of - Ow).max() < 1e-14 and np.abs(Lf - Lw).max() < 1e-14
+    O0, L0 = A.window_attention_fwd(q, k, v, scale, c, 0)
+    for p in range(P):
+        sl = slice(p * c, (p + 1) * c)
+        Oc, Lc = A.attention_fwd(q[:, sl], k[:, sl], v[:, sl], scale)
+        assert np.abs(O0[:, sl] - Oc).max() < 1e-14 and np.abs(L0[:, sl] - Lc).max() < 1e-14
+    # P = 8, window of one worker: the last worker's rows depend on chunks 6 and 7 only
+    c8 = 3
+    q8, k8, v8, _ = _case(43, 1, 1, 8 * c8, 4)
+    O1, _ = A.window_attention_fwd(q8, k8, v8, 0.5, c8, 1)
+    k8b, v8b = k8.copy(), v8.copy()
+    k8b[:, :6 * c8] += 3.0; v8b[:, :6 * c8] -= 2.0
+    O2, _ = A.window_attention_fwd(q8, k8b, v8b, 0.5, c8, 1)
+    assert np.array_equal(O1[:, 7 * c8:], O2[:, 7 * c8:])
+    assert not np.allclose(O1[:, 6 * c8:7 * c8], O2[:, 6 * c8:7 * c8])   # worker 6 does see chunk 5
+
+
+def test_window_backward_finite_differences_and_merge_of_pairs():
+    h_q, h_kv, c, P, d = 2, 1, 4, 3, 5
+    n = c * P
+    q, k, v, do = _case(47, h_q, h_kv, n, d)
+    scale, w = 0.37, 1
+
+    def loss(q_, k_, v_):
+        return float((A.window_attention_fwd(q_, k_, v_, scale, c, w)[0] * do).sum())
+
+    dq, dk, dv = A.window_attention_bwd(q, k, v, do, scale, c, w)
+    eps = 1e-6
+    rng = np.random.default_rng(1)
+    for arr, grad, idx in ((q, dq, 0), (k, dk, 1), (v, dv, 2)):
+        for _ in range(40):
+            pos = tuple(rng.integers(0, s) for s in arr.shape)
+            args = [q.copy(), k.copy(), v.copy()]
+            args[idx][pos] += eps
+            up = loss(*args)
+            args[idx][pos] -= 2 * eps
+            dn = loss(*args)
+            fd = (up - dn) / (2 * eps)
+            assert abs(fd - grad[pos]) <= 1e-7 * max(1.0, abs(fd)), (idx, pos, fd, grad[pos])
+    # the truncated schedule's pairs, merged, give the windowed attention; their backward
+    # contributions, summed, its gradients
+    O, L = A.window_attention_fwd(q, k, v, scale, c, w)
+    D = A.delta_rows(O, do)
+    gq, gk, gv = np.zeros_like(q), np.zeros_like(k), np.zeros_like(v)
+    for p in range(P):
+        o_p, l_p = A.pair_fwd(q, k, v, scale, p, p, c)
+        for r in range(max(0, p - w), p):
+            o_p, l_p = A.merge(o_p, l_p, *A.pair_fwd(q, k, v, scale, p, r, c))
+        assert np.abs(o_p - O[:, p * c:(p + 1) * c]).max() < 1e-13
+        assert np.abs(l_p - L[:, p * c:(p + 1) * c]).max() < 1e-13
+        for r in range(max(0, p - w), p + 1):
+            a, b, e = A.pair_bwd(q, k, v, do, L, D, scale, p, r, c)
+            gq[:, p * c:(p + 1) * c] += a; gk[:, r * c:(r + 1) * c] += b; gv[:, r * c:(r + 1) * c] += e
+    assert np.abs(gq - dq).max() < 1e-12 and np.abs(gk - dk).max() < 1e-12 and np.abs(gv - dv).max() < 1e-12

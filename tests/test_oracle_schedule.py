@@ -79,3 +79,17 @@ def test_tables_p4():
                      [S.DIAG, S.OWN, S.OWN], [S.DIAG, S.OWN, S.OWN]]
     assert (bal[0][1]["q_chunk"], bal[0][1]["kv_chunk"]) == (3, 0)
     assert bal[3][1]["recv_from"] == 0 and bal[3][2]["recv_from"] == -1
+
+
+@pytest.mark.parametrize("P,W", [(8, 1), (8, 3), (5, 0), (4, 7)])
+def test_window_schedule(P, W):
+    """Local sliding window (appendix on sparse patterns): worker w computes the pairs with the
+    min(w, W) preceding chunks and nothing else; the appendix's example (P = 8, window of one
+    worker: worker 7 attends to itself and worker 6) is the (8, 1) case."""
+    sched = S.window(P, W)
+    want = sorted((p, r) for p in range(P) for r in range(max(0, p - W), p + 1))
+    assert sorted(S.pairs(sched)) == want
+    assert all(len(w) == 1 + min(W, P - 1) for w in sched)
+    assert all(s["kind"] != S.HELP for w in sched for s in w)
+    if (P, W) == (8, 1):
+        assert [(s["q_chunk"], s["kv_chunk"]) for s in sched[7]] == [(7, 7), (7, 6)]
