@@ -212,6 +212,19 @@ def main():
                                                             "tflops": round(fw_fl / (fw_ms * 1e-3) / 1e12, 2),
                                                             "share_of_step": round(fw_ms / fw_n / ms, 3)}}}
 
+    # On-box ceiling of the matrix pipes (after the timed region): a register-resident MFMA stream
+    # at the clock the device sustains under that load, next to the published peak.
+    probe_out = torch.empty(512 * 256, dtype=torch.float32, device=dev)
+    B.dfa_mfma_probe(probe_out, 2000)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    probe_flop = B.dfa_mfma_probe(probe_out, 20000)
+    e1.record()
+    torch.cuda.synchronize()
+    ceiling = probe_flop / (e0.elapsed_time(e1) * 1e-3) / 1e12
+    roofline["onbox_mfma_ceiling"] = round(ceiling, 1)
+    roofline["frac_of_onbox_ceiling"] = round(achieved / ceiling, 4)
+
     out = {
         "metric": "causal-adjusted attention TFLOP/s fwd+bwd per worker share; % of bf16 MFMA peak",
         "value": round(tflops, 2), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
@@ -221,6 +234,7 @@ def main():
                                f"{len(remote)} remote merges, H={w.h_q}/{w.h_kv} d={w.d} C={c}",
                    "n_total": w.n_total, "P": w.p, "chunk": c},
         "pct_of_bf16_peak": round(100.0 * tflops / PEAK_BF16_TFLOPS, 2),
+        "pct_of_onbox_mfma_ceiling": round(100.0 * tflops / ceiling, 2),
         "flop_per_step": flops_step,
         "roofline": roofline,
     }

@@ -173,6 +173,24 @@ int dfa_schedule(int32_t P, int32_t worker_id, dfa_step* out, int32_t cap);
  * P steps, no helpers. Returns the number of steps. */
 int dfa_schedule_mode(int32_t mode, int32_t P, int32_t worker_id, dfa_step* out, int32_t cap);
 
+/* Local sliding window (appendix on sparse patterns): attention restricted to the query's own
+ * chunk and the `window_chunks` chunks before it, i.e. the vanilla schedule with the end of its
+ * loop moved: step 0 is the diagonal chunk, step t in 1..min(window_chunks, P-1) the OWN pair
+ * with the chunk t positions earlier (idle for a worker with fewer earlier chunks); no helpers,
+ * the load is near balanced by itself.  window_chunks >= P-1 gives the vanilla schedule.
+ * Pure host function, `out` as for dfa_schedule; returns the number of steps
+ * 1 + min(window_chunks, P-1), or a negative dfa_status (window_chunks < 0: DFA_ERR_ARG). */
+int dfa_schedule_window(int32_t P, int32_t worker_id, int32_t window_chunks, dfa_step* out, int32_t cap);
+
+/* Measurement aid (no part of the method): launches a register-resident stream of bf16
+ * 32x32x16 MFMAs on every SIMD of the device (512 workgroups of 256 lanes, 4 * iters MFMAs per
+ * wavefront, no memory traffic in the loop) on `stream`.  Timed by the caller, *flop / time is
+ * the matrix throughput the device sustains at its clock under load, the on-box ceiling quoted
+ * next to the published peak.  `out`: DEVICE buffer of n_out >= 131072 floats, overwritten with
+ * values of no meaning; `flop`: HOST pointer receiving the FLOP count of the launch (may be NULL).
+ * Errors: DFA_ERR_NULL (out), DFA_ERR_ARG (iters < 1 or n_out too small), DFA_ERR_HIP. */
+int dfa_mfma_probe(float* out, int64_t n_out, int32_t iters, double* flop, void* stream);
+
 /* Human-readable name of a dfa_status (static storage, host). */
 const char* dfa_status_str(int status);
 

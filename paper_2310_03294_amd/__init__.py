@@ -12,6 +12,7 @@ from .binding import (  # noqa: F401
     dfa_chunk_fwd_acc,
     dfa_delta,
     dfa_merge,
+    dfa_mfma_probe,
     dfa_schedule,
     dfa_status_str,
     dfa_version,

@@ -52,7 +52,7 @@ class DfaStep(ctypes.Structure):
 Step = collections.namedtuple("Step", "t kind q_chunk kv_chunk send_to recv_from")
 
 EXPORTS = ("dfa_chunk_fwd", "dfa_chunk_fwd_acc", "dfa_merge", "dfa_delta", "dfa_chunk_bwd", "dfa_schedule",
-           "dfa_schedule_mode", "dfa_status_str", "dfa_version")
+           "dfa_schedule_mode", "dfa_schedule_window", "dfa_mfma_probe", "dfa_status_str", "dfa_version")
 
 
 def lib_path() -> str:
@@ -78,6 +78,9 @@ def load_library():
     lib.dfa_chunk_bwd.argtypes = [shp, vp, vp, vp, vp, vp, vp, vp, vp, vp, ctypes.c_int, vp]
     lib.dfa_schedule.argtypes = [i32, i32, ctypes.POINTER(DfaStep), i32]
     lib.dfa_schedule_mode.argtypes = [i32, i32, i32, ctypes.POINTER(DfaStep), i32]
+    lib.dfa_schedule_window.argtypes = [i32, i32, i32, ctypes.POINTER(DfaStep), i32]
+    lib.dfa_mfma_probe.argtypes = [ctypes.c_void_p, ctypes.c_int64, i32, ctypes.POINTER(ctypes.c_double),
+                                   ctypes.c_void_p]
     lib.dfa_status_str.argtypes = [ctypes.c_int]
     lib.dfa_status_str.restype = ctypes.c_char_p
     lib.dfa_version.argtypes = []
@@ -233,13 +236,27 @@ def dfa_chunk_bwd(q, k, v, lse, delta, dO, dq, dk, dv, causal, scale, accumulate
     return dq, dk, dv
 
 
-def dfa_schedule(P: int, worker_id: int, mode: str = "balanced"):
-    """Step list of one worker (host integers only)."""
+def dfa_mfma_probe(out, iters: int, stream=None) -> float:
+    """Launches the register-resident MFMA stream (measurement aid); returns its FLOP count."""
     lib = load_library()
-    m = {"balanced": 0, "ring": 1}[mode]
+    flop = ctypes.c_double(0.0)
+    _check(lib.dfa_mfma_probe(out.data_ptr(), out.numel(), int(iters), ctypes.byref(flop), _stream(stream)),
+           "dfa_mfma_probe")
+    return flop.value
+
+
+def dfa_schedule(P: int, worker_id: int, mode="balanced"):
+    """Step list of one worker (host integers only).  mode: "balanced", "ring", or
+    ("window", window_chunks) for the local sliding window (dfa_schedule_window)."""
+    lib = load_library()
     cap = max(1, P + 1)
     buf = (DfaStep * cap)()
-    n = lib.dfa_schedule_mode(m, P, worker_id, buf, cap)
+    if isinstance(mode, tuple):
+        if mode[0] != "window":
+            raise ValueError(mode)
+        n = lib.dfa_schedule_window(P, worker_id, int(mode[1]), buf, cap)
+    else:
+        n = lib.dfa_schedule_mode({"balanced": 0, "ring": 1}[mode], P, worker_id, buf, cap)
     if n < 0:
         raise DfaError(n, "dfa_schedule")
     return [Step(b.t, b.kind, b.q_chunk, b.kv_chunk, b.send_to, b.recv_from) for b in buf[:n]]

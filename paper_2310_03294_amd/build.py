@@ -20,6 +20,7 @@ SOURCES = (
     "dfa_attn_f32.hip",
     "dfa_fwd_bf16.hip",
     "dfa_bwd_bf16.hip",
+    "dfa_probe.hip",
 )
 
 HIP_FLAGS = (

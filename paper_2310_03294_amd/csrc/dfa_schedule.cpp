@@ -37,6 +37,19 @@ extern "C" int dfa_schedule_mode(int32_t mode, int32_t P, int32_t w, dfa_step* o
   return n;
 }
 
+// Appendix on sparse patterns, local sliding windows: only the end of the vanilla loop changes.
+extern "C" int dfa_schedule_window(int32_t P, int32_t w, int32_t window_chunks, dfa_step* out, int32_t cap) {
+  if (P < 1 || w < 0 || w >= P || cap < 0 || window_chunks < 0) return DFA_ERR_ARG;
+  if (cap > 0 && out == nullptr) return DFA_ERR_NULL;
+  const int n = 1 + (window_chunks < P - 1 ? window_chunks : P - 1);
+  for (int t = 0; t < n && t < cap; ++t) {
+    if (t == 0) fill(&out[t], 0, DFA_STEP_DIAG, w, w, -1, -1);
+    else if (t <= w) fill(&out[t], t, DFA_STEP_OWN, w, w - t, -1, -1);
+    else fill(&out[t], t, DFA_STEP_IDLE, -1, -1, -1, -1);
+  }
+  return n;
+}
+
 extern "C" int dfa_schedule(int32_t P, int32_t w, dfa_step* out, int32_t cap) {
   return dfa_schedule_mode(DFA_SCHED_BALANCED, P, w, out, cap);
 }

@@ -50,6 +50,26 @@ def test_schedule_matches_oracle(lib, P):
                 assert g._asdict() == r
 
 
+@pytest.mark.parametrize("P", [1, 2, 5, 8, 16])
+def test_window_schedule_matches_oracle(lib, P):
+    for W in (0, 1, 3, P - 1, P + 4):
+        ref = S.window(P, W)
+        for w in range(P):
+            got = dfa.dfa_schedule(P, w, ("window", W))
+            assert [g._asdict() for g in got] == ref[w]
+    buf = (B.DfaStep * 2)()
+    assert lib.dfa_schedule_window(P, 0, -1, buf, 2) == -4
+    assert lib.dfa_schedule_window(P, P, 1, buf, 2) == -4
+    assert lib.dfa_schedule_window(P, 0, 1, None, 2) == -1
+
+
+def test_mfma_probe_rejects_bad_arguments_before_any_launch(lib):
+    flop = ctypes.c_double(0)
+    assert lib.dfa_mfma_probe(None, 1 << 20, 10, ctypes.byref(flop), None) == -1
+    assert lib.dfa_mfma_probe(ctypes.c_void_p(256), 1 << 20, 0, ctypes.byref(flop), None) == -4
+    assert lib.dfa_mfma_probe(ctypes.c_void_p(256), 1000, 10, ctypes.byref(flop), None) == -4
+
+
 def test_schedule_errors_and_cap(lib):
     buf = (B.DfaStep * 2)()
     assert lib.dfa_schedule(0, 0, buf, 2) == -4

@@ -196,8 +196,12 @@ def _schedule_case(w: dfa_inputs.Workload, mode="balanced", fused=True):
     driver.run_all_workers(Q, K, V, dO, w.scale, w.p, bufs, mode=mode, fused=fused)
     torch.cuda.synchronize()
     q64, k64, v64, do64 = (np64(t) for t in (q, k, v, do))
-    O, L = A.attention_fwd(q64, k64, v64, w.scale)
-    dQ, dK, dV = A.attention_bwd(q64, k64, v64, do64, w.scale)
+    if isinstance(mode, tuple):     # ("window", W): attention local to the W preceding chunks
+        O, L = A.window_attention_fwd(q64, k64, v64, w.scale, w.n_total // w.p, mode[1])
+        dQ, dK, dV = A.window_attention_bwd(q64, k64, v64, do64, w.scale, w.n_total // w.p, mode[1])
+    else:
+        O, L = A.attention_fwd(q64, k64, v64, w.scale)
+        dQ, dK, dV = A.attention_bwd(q64, k64, v64, do64, w.scale)
     tol = TOL[w.torch_dtype]
     errs = dict(o=maxerr(bufs.O, O), lse=maxerr(bufs.L, L), dq=maxerr(bufs.dQ, dQ), dk=maxerr(bufs.dK, dK),
                 dv=maxerr(bufs.dV, dV))
@@ -215,6 +219,17 @@ def test_config1_full_balanced_schedule(fused):
 @pytest.mark.parametrize("fused", [True, False])
 def test_config1_ring_schedule(fused):
     _schedule_case(dfa_inputs.CONFIGS[0], mode="ring", fused=fused)
+
+
+@pytest.mark.parametrize("W", [0, 1, 2, 9])
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_window_schedule(W, dtype):
+    """Local sliding window at chunk granularity (appendix on sparse patterns): the truncated
+    schedule's merged outputs and summed gradients against the oracle's windowed attention."""
+    w = dfa_inputs.Workload(f"t_win{W}", 4, 2, 128, 160 * 5, 5, dtype, 777 + W)
+    _schedule_case(w, mode=("window", W))
+    if W == 1:
+        _schedule_case(w, mode=("window", W), fused=False)
 
 
 @pytest.mark.parametrize("P", [1, 2, 3, 5, 8])
@@ -331,3 +346,11 @@ def test_forward_running_maximum_moves(causal):
     scale_of = dict(o=1.0, lse=1.0, o_acc=1.0, lse_acc=1.0, dq=max(1.0, np.abs(rq).max()),
                     dk=max(1.0, np.abs(rk).max()), dv=max(1.0, np.abs(rv).max()))
     assert all(errs[n] <= tol * scale_of[n] for n in errs), (errs, scale_of)
+
+
+def test_mfma_probe_runs_and_counts_its_flop():
+    out = torch.empty(512 * 256, dtype=torch.float32, device=dev())
+    flop = dfa.dfa_mfma_probe(out, 100)
+    torch.cuda.synchronize()
+    assert flop == 2.0 * 32 * 32 * 16 * 4 * 100 * 2048
+    assert bool(torch.isfinite(out).all())
