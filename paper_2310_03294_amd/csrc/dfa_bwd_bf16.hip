@@ -9,7 +9,8 @@
 //  one of each kind per SIMD, so that the exponentials of one overlap the MFMAs of the other:
 //    "S" wavefront  (K^T in registers):  S = Q K^T, P = exp2(S c - lse log2e), hands P (bf16)
 //                                        to its partner through LDS, dV^T += dO^T P
-//    "dP" wavefront (V^T in registers):  dP = dO V^T, dS = P o (dP - D), dK^T += Q^T dS
+//    "dP" wavefront (V^T in registers):  dP - D = dO V^T - D (the MFMA chains start from -D),
+//                                        dS = P o (dP - D), dK^T += Q^T dS
 //  (queries x keys tiles on v_mfma_f32_32x32x16_bf16: each lane holds 16 queries of ONE key; P
 //  and dS are fed back from registers as B operands; dO^T, Q^T are gathered from LDS with the
 //  transposing read).  The dP wavefronts run one tile behind, so one barrier per tile suffices.
@@ -106,19 +107,16 @@ __device__ __forceinline__ void qtile_load_ld(QTileRegs& t, const QTileCursor& c
 __device__ __forceinline__ void qtile_store(const QTileRegs& t, float* LDs, int tid) {
   if (tid < 64)   // lse pre-multiplied by log2 e; +inf makes P exactly 0 for an absent or empty row
     LDs[tid] = (t.ld_ok && t.ld > -INFINITY) ? t.ld * LOG2E : INFINITY;
-  else if (tid < 128)
-    LDs[tid] = t.ld_ok ? t.ld : 0.f;
+  else if (tid < 128)   // -D: the value the dP accumulators start from
+    LDs[tid] = t.ld_ok ? -t.ld : 0.f;
 }
 
-// C[qb] = X[qb rows] * B^T over d for both 32-row blocks of the tile: X rows are read from LDS
-// (A operand), B is the wavefront's K^T or V^T held in registers.
+// C[qb] = I[qb] + X[qb rows] * B^T over d for both 32-row blocks of the tile: X rows are read from
+// LDS (A operand), B is the wavefront's K^T or V^T held in registers, I the values the chains start from.
 __device__ __forceinline__ void row_products(f32x16& c0, f32x16& c1, const char* Xs, int a_base,
-                                             const bf16x8 (&bT)[8]) {
+                                             const bf16x8 (&bT)[8], const f32x16& i0, const f32x16& i1) {
   constexpr int AHEAD = 3;                      // LDS reads run this many d-steps ahead of the MFMAs
   bf16x8 x0[AHEAD + 1], x1[AHEAD + 1];
-  f32x16 zero;
-#pragma unroll
-  for (int j = 0; j < 16; ++j) zero[j] = 0.f;
 #pragma unroll
   for (int ks = 0; ks < AHEAD; ++ks) {
     x0[ks] = lds_read_b128(Xs, a_base + ks * 32);
@@ -131,8 +129,8 @@ __device__ __forceinline__ void row_products(f32x16& c0, f32x16& c1, const char*
       x0[(ks + AHEAD) % (AHEAD + 1)] = lds_read_b128(Xs, a_base + (ks + AHEAD) * 32);
       x1[(ks + AHEAD) % (AHEAD + 1)] = lds_read_b128(Xs, a_base + 32 * kRowBytes + (ks + AHEAD) * 32);
     }
-    c0 = mfma32(x0[ks % (AHEAD + 1)], bT[ks], ks == 0 ? zero : c0);
-    c1 = mfma32(x1[ks % (AHEAD + 1)], bT[ks], ks == 0 ? zero : c1);
+    c0 = mfma32(x0[ks % (AHEAD + 1)], bT[ks], ks == 0 ? i0 : c0);
+    c1 = mfma32(x1[ks % (AHEAD + 1)], bT[ks], ks == 0 ? i1 : c1);
     DFA_SCHED_FENCE();
   }
 }
@@ -255,6 +253,9 @@ __global__ void __launch_bounds__(NT, 2) k_bwd_dkdv_bf16(BwdParams p) {
                smem + OFF_G + (((IT) + 1) & 1) * QTILE_BYTES, kb, lane);                         \
   }
 
+  f32x16 zero;
+#pragma unroll
+  for (int j = 0; j < 16; ++j) zero[j] = 0.f;
   if (!dp_wave) {
     for (int it = 0; it < niter; ++it) {
       const bool more = it + 1 < niter;
@@ -265,7 +266,7 @@ __global__ void __launch_bounds__(NT, 2) k_bwd_dkdv_bf16(BwdParams p) {
       const int q0 = q_begin + (it % ntq) * BM;
       if (more) DFA_STAGE(it, next)
       f32x16 c0, c1;
-      row_products(c0, c1, Qs, a_base, bT);          // S = Q K^T
+      row_products(c0, c1, Qs, a_base, bT, zero, zero);          // S = Q K^T
       // Only the causal diagonal needs a mask: query rows past s_q carry lse' = +inf (P = 0)
       // and key rows past s_k only feed dk/dv rows that are never written.
       if (p.causal && q0 < k0 + BN - 1) {
@@ -303,39 +304,47 @@ __global__ void __launch_bounds__(NT, 2) k_bwd_dkdv_bf16(BwdParams p) {
   } else {
     f32x16 c0, c1;        // dP of the tile in flight, carried over the barrier
     bf16x8 w[2][2];
-    auto dS_prev = [&](int it, int prev) {           // dS of tile it - 1 from P (LDS) and dP (registers)
-      const float* Ds = reinterpret_cast<const float*>(smem + OFF_LD + prev * LD_BYTES) + 64;
+    // -D of a tile's 64 query rows in the accumulator layout: the dP chains start from it, so what
+    // they end with is dP - D
+    auto neg_d = [&](f32x16& d0, f32x16& d1, int ld_slot) {
+      const float* Ds = reinterpret_cast<const float*>(smem + OFF_LD + ld_slot * LD_BYTES) + 64;
+#pragma unroll
+      for (int g4 = 0; g4 < 4; ++g4) {
+        const f32x4 a = *reinterpret_cast<const f32x4*>(Ds + g4 * 8 + hh * 4);
+        const f32x4 b = *reinterpret_cast<const f32x4*>(Ds + 32 + g4 * 8 + hh * 4);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) { d0[g4 * 4 + e] = a[e]; d1[g4 * 4 + e] = b[e]; }
+      }
+    };
+    auto dS_prev = [&](int it) {                     // dS of tile it - 1 from P (LDS) and dP - D (registers)
       const char* px = smem + OFF_PX + ((it & 1) ^ 1) * PX_BYTES + kb * 4096 + lane * 16;
 #pragma unroll
       for (int j = 0; j < 4; ++j) w[j >> 1][j & 1] = *reinterpret_cast<const bf16x8*>(px + j * 1024);
 #pragma unroll
-      for (int g4 = 0; g4 < 4; ++g4) {
-        const f32x4 d0 = *reinterpret_cast<const f32x4*>(Ds + g4 * 8 + hh * 4);
-        const f32x4 d1 = *reinterpret_cast<const f32x4*>(Ds + 32 + g4 * 8 + hh * 4);
-#pragma unroll
-        for (int e = 0; e < 4; ++e) {
-          const int j = g4 * 4 + e;
-          c0[j] = static_cast<float>(w[0][j >> 3][j & 7]) * (c0[j] - d0[e]);
-          c1[j] = static_cast<float>(w[1][j >> 3][j & 7]) * (c1[j] - d1[e]);
-        }
+      for (int j = 0; j < 16; ++j) {
+        c0[j] = static_cast<float>(w[0][j >> 3][j & 7]) * c0[j];
+        c1[j] = static_cast<float>(w[1][j >> 3][j & 7]) * c1[j];
       }
       w[0][0] = pack8(c0, 0); w[0][1] = pack8(c0, 8);
       w[1][0] = pack8(c1, 0); w[1][1] = pack8(c1, 8);
     };
+    f32x16 d0, d1;
     {  // slot 0: dP of tile 0 only
-      row_products(c0, c1, smem + OFF_G, a_base, bT);
+      neg_d(d0, d1, 0);
+      row_products(c0, c1, smem + OFF_G, a_base, bT, d0, d1);
       __syncthreads();
       slot = 1;
     }
     for (int it = 1; it < niter; ++it) {
       const int prev = slot == 0 ? 2 : slot - 1, next = slot == 2 ? 0 : slot + 1;
-      dS_prev(it, prev);
+      neg_d(d0, d1, slot);
+      dS_prev(it);
       col_products(acc, smem + OFF_Q + prev * QTILE_BYTES, g_base, w);           // dK^T += Q^T dS
-      row_products(c0, c1, smem + OFF_G + (it & 1) * QTILE_BYTES, a_base, bT);   // dP = dO V^T
+      row_products(c0, c1, smem + OFF_G + (it & 1) * QTILE_BYTES, a_base, bT, d0, d1);   // dP - D = dO V^T - D
       __syncthreads();
       slot = next;
     }
-    dS_prev(niter, slot == 0 ? 2 : slot - 1);
+    dS_prev(niter);
     col_products(acc, smem + OFF_Q + (slot == 0 ? 2 : slot - 1) * QTILE_BYTES, g_base, w);
     __syncthreads();
   }
@@ -418,6 +427,11 @@ __global__ void __launch_bounds__(NTHREADS, 2) k_bwd_dq_bf16(BwdParams p) {
     Dr = p.delta[head * p.l_sh + qrow];
   }
 
+  // -D of the lane's query row in every element: the accumulator the dP^T products start from,
+  // which saves the subtraction per score
+  f32x16 negD;
+#pragma unroll
+  for (int j = 0; j < 16; ++j) negD[j] = -Dr;
   f32x16 dqT[4];
 #pragma unroll
   for (int i = 0; i < 4; ++i)
@@ -454,7 +468,7 @@ __global__ void __launch_bounds__(NTHREADS, 2) k_bwd_dq_bf16(BwdParams p) {
         bf16x8 ka[4], va[4];
         f32x16 s, dp;
 #pragma unroll
-        for (int j = 0; j < 16; ++j) { s[j] = 0.f; dp[j] = 0.f; }
+        for (int j = 0; j < 16; ++j) s[j] = 0.f;
 #pragma unroll
         for (int ks = 0; ks < 4; ++ks) {
           const int off = a_base + nb * 32 * kRowBytes + ks * 32;
@@ -465,7 +479,7 @@ __global__ void __launch_bounds__(NTHREADS, 2) k_bwd_dq_bf16(BwdParams p) {
 #pragma unroll
         for (int ks = 0; ks < 8; ++ks) {
           s = mfma32(ka[ks & 3], qB[ks], s);
-          dp = mfma32(va[ks & 3], gB[ks], dp);
+          dp = mfma32(va[ks & 3], gB[ks], ks == 0 ? negD : dp);      // the chain starts from -D
           if (ks < 4) {
             const int off = a_base + nb * 32 * kRowBytes + (ks + 4) * 32;
             ka[ks & 3] = lds_read_b128(Ks, off);
@@ -473,11 +487,11 @@ __global__ void __launch_bounds__(NTHREADS, 2) k_bwd_dq_bf16(BwdParams p) {
           }
           DFA_SCHED_FENCE();
         }
-        // dS^T = P^T o (dP^T - D): lse' and D are per-lane scalars here
+        // dS^T = P^T o (dP^T - D): lse' is a per-lane scalar here, -D came in through the accumulator
 #pragma unroll
         for (int j = 0; j < 16; ++j) {
           const float pr = __builtin_amdgcn_exp2f(fmaf(s[j], c2, -Lr));
-          dp[j] = pr * (dp[j] - Dr);
+          dp[j] = pr * dp[j];
         }
         if (need_mask) {
 #pragma unroll
