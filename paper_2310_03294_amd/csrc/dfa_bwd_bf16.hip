@@ -14,6 +14,8 @@
 //  (queries x keys tiles on v_mfma_f32_32x32x16_bf16: each lane holds 16 queries of ONE key; P
 //  and dS are fed back from registers as B operands; dO^T, Q^T are gathered from LDS with the
 //  transposing read).  The dP wavefronts run one tile behind, so one barrier per tile suffices.
+//  Wavefronts raise their priority while they issue MFMAs, so that the other kind's VALU work
+//  fills the gaps instead of delaying them.
 //  dv / dk are written once per workgroup (summed over the group's query heads in registers).
 //
 //  k_bwd_dq_bf16 (query-stationary).  A workgroup of 4 wavefronts owns 128 query rows of one head
@@ -52,7 +54,7 @@ constexpr int NT = 512;     // 8 wavefronts: 4 "S" wavefronts (dV) and 4 "dP" wa
 constexpr int BN = 128;     // key rows per workgroup, 32 per wavefront pair
 constexpr int BM = 64;      // query rows per LDS tile
 constexpr int QTILE_BYTES = BM * kRowBytes;   // rows padded to 272 B
-constexpr int LD_BYTES = 512;                 // lse'[64] then D[64]
+constexpr int LD_BYTES = 1024;                // lse'[64], -D[64], 128 spare floats
 constexpr int PX_BYTES = 4 * 4096;            // P hand-over: 4 key blocks x (64 x 32 bf16)
 // LDS map.  Tile t lives in Q slot t % 3, dO slot t % 2, lse/D slot t % 3, P slot t % 2.
 constexpr int OFF_Q = 0;
@@ -63,11 +65,14 @@ constexpr int SMEM_BYTES = OFF_PX + 2 * PX_BYTES;
 
 // The Q and dO tiles go from global memory straight into LDS (global_load_lds_dwordx4: every
 // lane supplies its own global address, the wavefront's 64 x 16 bytes land contiguously at the
-// LDS address in M0).  A padded tile is 17 such 1 KB pieces; S wavefront w moves pieces w, w + 4,
-// w + 8, w + 12 and (w = 0 only) 16.  Byte 16 s of the tile is chunk s % 17 of physical row
-// s / 17; chunk 16 is the pad (it receives a copy of chunk 15).  Only lse / D pass through a
-// register.  The copies are issued from inline assembly (see lds_dma16): the S wavefronts, which
-// have slack, issue them at the top of a slot and wait for them just before the slot's barrier.
+// LDS address in M0).  A padded tile is 17 such 1 KB pieces; of the four wavefronts that copy a
+// tile, wavefront w moves pieces 4w .. 4w + 3 and (w = 0 only) 16.  Byte 16 s of the tile is chunk
+// s % 17 of physical row s / 17; chunk 16 is the pad (it receives a copy of chunk 15).  Only
+// lse / D pass through a register.  The S wavefronts copy the Q tiles, the dP wavefronts the dO
+// tiles, each piece issued from inline assembly between two MFMAs of a product (the memory pipe
+// takes ~17 cycles per piece and CU: issued in a burst, the pieces stall the wavefront) and waited
+// for just before the slot's barrier.  Measured with time stamps per phase: all staging at the top
+// of the slot cost the S wavefronts, which are the critical path, 600-900 of ~3500 cycles per tile.
 struct QTileRegs { float ld; bool ld_ok; };
 
 // Where the next (Q, dO, lse, D) tile comes from: wave-uniform head bases, advanced tile by
@@ -86,6 +91,16 @@ __device__ __forceinline__ void qtile_advance(QTileCursor& cur, const BwdParams&
     cur.qh += p.q_sh * 2; cur.gh += p.q_sh * 2; cur.ldh += p.l_sh;
   }
 }
+// The same as selects only (adv false: the cursor stays), for use inside the straight-line loops.
+__device__ __forceinline__ void qtile_advance_if(QTileCursor& cur, bool adv, const BwdParams& p, int q_begin,
+                                                 int q_end) {
+  const int nq = cur.q0 + 64;
+  const bool wrap = nq >= q_end;
+  const int64_t hs = (adv && wrap) ? p.q_sh * 2 : 0;
+  const int64_t ls = (adv && wrap) ? p.l_sh : 0;
+  cur.q0 = adv ? (wrap ? q_begin : nq) : cur.q0;
+  cur.qh += hs; cur.gh += hs; cur.ldh += ls;
+}
 
 // Rows past s_q are clamped to the last row instead of zero-filled: their lse' is +inf, so P and
 // dS vanish for them whatever (finite) Q and dO the tile holds.  Qs, Gs: LDS tiles to fill.
@@ -96,7 +111,9 @@ __device__ __forceinline__ void qtile_copy(const QTileCursor& cur, const TileLan
   tile_dma(cur.gh, rowbytes, cur.q0, p.s_q - 1, m, Gs, w, lane);
 }
 
-// lse (even wavefronts) or D (odd wavefronts) of the tile's 64 rows, one per lane, into a register.
+// lse (S wavefronts 0, 2, 3) or D (S wavefront 1) of the tile's 64 rows, one per lane, into a
+// register.  Wavefronts 2 and 3 only go through the motions (their values land in a spare part
+// of the slot), which keeps the staging free of branches.
 __device__ __forceinline__ void qtile_load_ld(QTileRegs& t, const QTileCursor& cur, const BwdParams& p, int tid) {
   const int last = p.s_q - 1;
   const int r = cur.q0 + (tid & 63);
@@ -104,17 +121,22 @@ __device__ __forceinline__ void qtile_load_ld(QTileRegs& t, const QTileCursor& c
   t.ld = cur.ldh[static_cast<uint32_t>(min(r, last))];
 }
 
-__device__ __forceinline__ void qtile_store(const QTileRegs& t, float* LDs, int tid) {
-  if (tid < 64)   // lse pre-multiplied by log2 e; +inf makes P exactly 0 for an absent or empty row
-    LDs[tid] = (t.ld_ok && t.ld > -INFINITY) ? t.ld * LOG2E : INFINITY;
-  else if (tid < 128)   // -D: the value the dP accumulators start from
-    LDs[tid] = t.ld_ok ? -t.ld : 0.f;
+// LDs: the slot's 256 floats: lse'[64], -D[64], 128 spare.
+__device__ __forceinline__ void qtile_store(const QTileRegs& t, float* LDs, int tid, bool is_d) {
+  // lse pre-multiplied by log2 e; +inf makes P exactly 0 for an absent or empty row
+  const float l = (t.ld_ok && t.ld > -INFINITY) ? t.ld * LOG2E : INFINITY;
+  const float d = t.ld_ok ? -t.ld : 0.f;      // -D: the value the dP accumulators start from
+  LDs[tid] = is_d ? d : l;
 }
 
-// C[qb] = I[qb] + X[qb rows] * B^T over d for both 32-row blocks of the tile: X rows are read from
-// LDS (A operand), B is the wavefront's K^T or V^T held in registers, I the values the chains start from.
+// C[qb] += X[qb rows] * B^T over d for both 32-row blocks of the tile: X rows are read from LDS
+// (A operand), B is the wavefront's K^T or V^T held in registers; the caller sets what the chains
+// start from (zero, or -D for the dP products).
+struct NoHook { __device__ __forceinline__ void operator()(int) const {} };
+// hook(ks) runs after the MFMAs of step ks (the callers issue their tile-copy pieces there)
+template <class Hook = NoHook>
 __device__ __forceinline__ void row_products(f32x16& c0, f32x16& c1, const char* Xs, int a_base,
-                                             const bf16x8 (&bT)[8], const f32x16& i0, const f32x16& i1) {
+                                             const bf16x8 (&bT)[8], Hook hook = Hook()) {
   constexpr int AHEAD = 3;                      // LDS reads run this many d-steps ahead of the MFMAs
   bf16x8 x0[AHEAD + 1], x1[AHEAD + 1];
 #pragma unroll
@@ -129,8 +151,9 @@ __device__ __forceinline__ void row_products(f32x16& c0, f32x16& c1, const char*
       x0[(ks + AHEAD) % (AHEAD + 1)] = lds_read_b128(Xs, a_base + (ks + AHEAD) * 32);
       x1[(ks + AHEAD) % (AHEAD + 1)] = lds_read_b128(Xs, a_base + 32 * kRowBytes + (ks + AHEAD) * 32);
     }
-    c0 = mfma32(x0[ks % (AHEAD + 1)], bT[ks], ks == 0 ? i0 : c0);
-    c1 = mfma32(x1[ks % (AHEAD + 1)], bT[ks], ks == 0 ? i1 : c1);
+    c0 = mfma32(x0[ks % (AHEAD + 1)], bT[ks], c0);
+    c1 = mfma32(x1[ks % (AHEAD + 1)], bT[ks], c1);
+    hook(ks);
     DFA_SCHED_FENCE();
   }
 }
@@ -138,24 +161,37 @@ __device__ __forceinline__ void row_products(f32x16& c0, f32x16& c1, const char*
 // acc[db] += Y^T[db block of d][64 queries] * W[64 queries][32 keys]: Y^T is gathered from the
 // row-major LDS tile with the transposing read, W (P or dS) comes from registers in the order
 // an MFMA result tile has (w[qb][half] = rows (e/4)*8 + 4h + e%4 of 16-row half `half`).
-__device__ __forceinline__ void col_products(f32x16 (&acc)[4], const char* Ys, int g_base,
-                                             const bf16x8 (&w)[2][2]) {
-  constexpr int AHEAD = 4;
-  bf16x8 y[AHEAD + 1];
-  auto off = [&](int n) {                 // n = qb * 8 + half * 4 + db
-    return g_base + ((n >> 3) * 32 + ((n >> 2) & 1) * 16) * kRowBytes + (n & 3) * 64;
-  };
+constexpr int COL_AHEAD = 4;              // gathers run this many MFMAs ahead
+__device__ __forceinline__ int col_off(int g_base, int n) {       // n = qb * 8 + half * 4 + db
+  return g_base + ((n >> 3) * 32 + ((n >> 2) & 1) * 16) * kRowBytes + (n & 3) * 64;
+}
+// The first COL_AHEAD gathers of col_products, issued early (e.g. before a barrier) so that the
+// products can start without waiting for LDS.
+// (The pieces are kept as raw 32-bit vectors: carried around a loop as bf16 vectors they would be
+// taken apart into 16-bit halves and put together again.)
+__device__ __forceinline__ void col_prefetch(u32x4 (&y)[COL_AHEAD + 1], const char* Ys, int g_base) {
 #pragma unroll
-  for (int n = 0; n < AHEAD; ++n) y[n] = lds_gather(Ys, off(n));
+  for (int n = 0; n < COL_AHEAD; ++n) y[n] = __builtin_bit_cast(u32x4, lds_gather(Ys, col_off(g_base, n)));
+}
+template <bool PRE, class Hook = NoHook>
+__device__ __forceinline__ void col_products(f32x16 (&acc)[4], const char* Ys, int g_base,
+                                             const bf16x8 (&w)[2][2], u32x4 (&y)[COL_AHEAD + 1],
+                                             Hook hook = Hook()) {
+  constexpr int AHEAD = COL_AHEAD;
+  if (!PRE) col_prefetch(y, Ys, g_base);
   DFA_SCHED_FENCE();
 #pragma unroll
   for (int n = 0; n < 16; ++n) {
-    if (n + AHEAD < 16) y[(n + AHEAD) % (AHEAD + 1)] = lds_gather(Ys, off(n + AHEAD));
-    acc[n & 3] = mfma32(y[n % (AHEAD + 1)], w[n >> 3][(n >> 2) & 1], acc[n & 3]);
+    if (n + AHEAD < 16)
+      y[(n + AHEAD) % (AHEAD + 1)] = __builtin_bit_cast(u32x4, lds_gather(Ys, col_off(g_base, n + AHEAD)));
+    acc[n & 3] = mfma32(__builtin_bit_cast(bf16x8, y[n % (AHEAD + 1)]), w[n >> 3][(n >> 2) & 1], acc[n & 3]);
+    hook(n);
     DFA_SCHED_FENCE();
   }
 }
 
+// RAGGED: s_q is no multiple of the 64-row tile, so a head's last tile has rows past the end.
+template <bool RAGGED>
 __global__ void __launch_bounds__(NT, 2) k_bwd_dkdv_bf16(BwdParams p) {
   extern __shared__ __align__(16) char smem[];
 
@@ -204,26 +240,27 @@ __global__ void __launch_bounds__(NT, 2) k_bwd_dkdv_bf16(BwdParams p) {
   const int ntq = (p.s_q - q_begin + BM - 1) / BM;  // query tiles per head for this key tile
   const int niter = ntq * p.group;
 
-  // Tile staging (S wavefronts only).  Two cursors: `cur` for the Q/dO copies (tile t + 1 during
-  // slot t), `curl` for lse / D, which pass through a register and run one tile further ahead.
-  // Order inside a slot: store the held lse / D, load the next ones, THEN issue the copies - the
-  // compiler knows nothing of the copies, so any wait it places for its own loads must come
-  // before them or it would wait for them too.
+  // Tile staging.  Two cursors: `cur` for the tile copies (tile t + 1 during slot t; Q by the S
+  // wavefronts, dO by the dP wavefronts), `curl` for lse / D (S wavefronts), which pass through a
+  // register and run one tile further ahead.  Order inside a slot: store the held lse / D, load
+  // the next ones, THEN issue the copies - the compiler knows nothing of the copies, so any wait
+  // it places for its own loads must come before them or it would wait for them too.
   QTileRegs tr;
   QTileCursor cur, curl;
   {
     const int hq0 = kh * p.group;
     cur.qh = reinterpret_cast<const char*>(p.q + hq0 * p.q_sh);
     cur.gh = reinterpret_cast<const char*>(p.dO + hq0 * p.q_sh);
-    cur.ldh = ((wave & 1) ? p.delta : p.lse) + hq0 * p.l_sh;
+    cur.ldh = (kb == 1 ? p.delta : p.lse) + hq0 * p.l_sh;
     cur.q0 = q_begin;
     curl = cur;
   }
   const int q_end = q_begin + ntq * BM;
-  const TileLane tl = tile_lane(kb, lane, static_cast<uint32_t>(p.q_ss) * 2);
+  const uint32_t q_rowbytes = static_cast<uint32_t>(p.q_ss) * 2;
+  const TileLane tl = tile_lane(kb, lane, q_rowbytes);
   if (!dp_wave) {
     qtile_load_ld(tr, curl, p, tid);
-    qtile_store(tr, reinterpret_cast<float*>(smem + OFF_LD), tid);
+    qtile_store(tr, reinterpret_cast<float*>(smem + OFF_LD), tid, kb == 1);
     if (niter > 1) {
       qtile_advance(curl, p, q_begin, q_end);
       qtile_load_ld(tr, curl, p, tid);           // lse / D of tile 1, stored in slot 0
@@ -239,34 +276,41 @@ __global__ void __launch_bounds__(NT, 2) k_bwd_dkdv_bf16(BwdParams p) {
   // the MFMAs of the other.  Both kinds run niter + 1 slots (the S wavefronts idle in the last,
   // the dP wavefronts have no dS/dK in the first); each kind has its own straight-line loop.
   int slot = 0;            // t % 3
-  // DFA_STAGE(IT, NEXT): lse / D of tile IT + 1 from the register into LDS, lse / D of tile IT + 2
-  // into the register, then the copies of tile IT + 1 into its ring slots.
-#define DFA_STAGE(IT, NEXT)                                                                      \
-  {                                                                                              \
-    qtile_store(tr, reinterpret_cast<float*>(smem + OFF_LD + (NEXT) * LD_BYTES), tid);           \
-    if ((IT) + 2 < niter) {                                                                      \
-      qtile_advance(curl, p, q_begin, q_end);                                                    \
-      qtile_load_ld(tr, curl, p, tid);                                                           \
-    }                                                                                            \
-    qtile_advance(cur, p, q_begin, q_end);                                                       \
-    qtile_copy(cur, tl, p, smem + OFF_Q + (NEXT) * QTILE_BYTES,                                  \
-               smem + OFF_G + (((IT) + 1) & 1) * QTILE_BYTES, kb, lane);                         \
-  }
-
   f32x16 zero;
 #pragma unroll
   for (int j = 0; j < 16; ++j) zero[j] = 0.f;
   if (!dp_wave) {
+    int q0 = q_begin;      // first query row of tile `it`
     for (int it = 0; it < niter; ++it) {
       const bool more = it + 1 < niter;
       const int next = slot == 2 ? 0 : slot + 1;
       const char* Qs = smem + OFF_Q + slot * QTILE_BYTES;
       const char* Gs = smem + OFF_G + (it & 1) * QTILE_BYTES;
       const float* Ls = reinterpret_cast<const float*>(smem + OFF_LD + slot * LD_BYTES);
-      const int q0 = q_begin + (it % ntq) * BM;
-      if (more) DFA_STAGE(it, next)
-      f32x16 c0, c1;
-      row_products(c0, c1, Qs, a_base, bT, zero, zero);          // S = Q K^T
+      // Staging, all of it inside the S products so that it costs no time of its own, and without
+      // branches (past the last tile the cursors stay: the same tile, lse and D go once more into
+      // ring slots nobody reads).  First (step 0) lse / D: tile it + 1 from the register into
+      // LDS, tile it + 2 into the register - before the first copy of the slot, because the
+      // compiler's wait for that register would otherwise wait for the copies too.  Then the Q
+      // tile it + 1 into ring slot `next`, one piece every other step.
+      qtile_advance_if(cur, more, p, q_begin, q_end);
+      const TileCopy cq = tile_copy_plan<RAGGED>(cur.qh, q_rowbytes, cur.q0, p.s_q - 1, tl,
+                                                 smem + OFF_Q + next * QTILE_BYTES, kb, lane);
+      f32x16 c0 = zero, c1 = zero;
+      __builtin_amdgcn_s_setprio(3);
+      row_products(c0, c1, Qs, a_base, bT, [&](int ks) {          // S = Q K^T
+        if (ks == 0) {
+          qtile_store(tr, reinterpret_cast<float*>(smem + OFF_LD + next * LD_BYTES), tid, kb == 1);
+          qtile_advance_if(curl, it + 2 < niter, p, q_begin, q_end);
+          qtile_load_ld(tr, curl, p, tid);
+        }
+        if (ks == 1) tile_copy_piece<0>(cq);
+        if (ks == 2 && kb == 0) tile_copy_piece<4>(cq);
+        if (ks == 3) tile_copy_piece<1>(cq);
+        if (ks == 5) tile_copy_piece<2>(cq);
+        if (ks == 7) tile_copy_piece<3>(cq);
+      });
+      __builtin_amdgcn_s_setprio(0);
       // Only the causal diagonal needs a mask: query rows past s_q carry lse' = +inf (P = 0)
       // and key rows past s_k only feed dk/dv rows that are never written.
       if (p.causal && q0 < k0 + BN - 1) {
@@ -295,10 +339,14 @@ __global__ void __launch_bounds__(NT, 2) k_bwd_dkdv_bf16(BwdParams p) {
 #pragma unroll
         for (int j = 0; j < 4; ++j) *reinterpret_cast<bf16x8*>(px + j * 1024) = w[j >> 1][j & 1];
       }
-      col_products(acc, Gs, g_base, w);              // dV^T += dO^T P
+      u32x4 y[COL_AHEAD + 1];
+      __builtin_amdgcn_s_setprio(3);
+      col_products<false>(acc, Gs, g_base, w, y);    // dV^T += dO^T P
+      __builtin_amdgcn_s_setprio(0);
       lds_dma_wait();                                // this wavefront's copies into LDS have landed
       __syncthreads();
       slot = next;
+      q0 = q0 + BM >= q_end ? q_begin : q0 + BM;
     }
     __syncthreads();      // the dP wavefronts' last slot
   } else {
@@ -328,28 +376,55 @@ __global__ void __launch_bounds__(NT, 2) k_bwd_dkdv_bf16(BwdParams p) {
       w[0][0] = pack8(c0, 0); w[0][1] = pack8(c0, 8);
       w[1][0] = pack8(c1, 0); w[1][1] = pack8(c1, 8);
     };
-    f32x16 d0, d1;
+    // The first Q^T gathers of the next slot's dK products are issued before the barrier (that Q
+    // tile has been in LDS for a whole slot), so after the barrier only P has to be waited for.
+    u32x4 y[COL_AHEAD + 1];
+    // The dP wavefronts copy the dO tiles: tile t + 1 during slot t, its pieces spread over the
+    // products (past the last tile the cursor stays: the same tile goes into the unused slot).
     {  // slot 0: dP of tile 0 only
-      neg_d(d0, d1, 0);
-      row_products(c0, c1, smem + OFF_G, a_base, bT, d0, d1);
-      __syncthreads();
+      qtile_advance_if(cur, niter > 1, p, q_begin, q_end);
+      const TileCopy cg = tile_copy_plan<RAGGED>(cur.gh, q_rowbytes, cur.q0, p.s_q - 1, tl,
+                                                 smem + OFF_G + QTILE_BYTES, kb, lane);
+      if (kb == 0) tile_copy_piece<4>(cg);
+      neg_d(c0, c1, 0);
+      row_products(c0, c1, smem + OFF_G, a_base, bT, [&](int ks) {
+        if (ks == 0) tile_copy_piece<0>(cg);
+        if (ks == 2) tile_copy_piece<1>(cg);
+        if (ks == 4) tile_copy_piece<2>(cg);
+        if (ks == 6) tile_copy_piece<3>(cg);
+      });
+      col_prefetch(y, smem + OFF_Q, g_base);
+      lds_dma_wait();
+      DFA_BARRIER_NO_DRAIN();
       slot = 1;
     }
     for (int it = 1; it < niter; ++it) {
       const int prev = slot == 0 ? 2 : slot - 1, next = slot == 2 ? 0 : slot + 1;
-      neg_d(d0, d1, slot);
+      qtile_advance_if(cur, it + 1 < niter, p, q_begin, q_end);
+      const TileCopy cg = tile_copy_plan<RAGGED>(cur.gh, q_rowbytes, cur.q0, p.s_q - 1, tl,
+                                                 smem + OFF_G + ((it + 1) & 1) * QTILE_BYTES, kb, lane);
+      if (kb == 0) tile_copy_piece<4>(cg);
+      __builtin_amdgcn_s_setprio(3);
       dS_prev(it);
-      col_products(acc, smem + OFF_Q + prev * QTILE_BYTES, g_base, w);           // dK^T += Q^T dS
-      row_products(c0, c1, smem + OFF_G + (it & 1) * QTILE_BYTES, a_base, bT, d0, d1);   // dP - D = dO V^T - D
-      __syncthreads();
+      neg_d(c0, c1, slot);                       // read straight into the accumulators, under the dK products
+      col_products<true>(acc, smem + OFF_Q + prev * QTILE_BYTES, g_base, w, y, [&](int n) {  // dK^T += Q^T dS
+        if (n == 1) tile_copy_piece<0>(cg);
+        if (n == 5) tile_copy_piece<1>(cg);
+        if (n == 9) tile_copy_piece<2>(cg);
+        if (n == 13) tile_copy_piece<3>(cg);
+      });
+      row_products(c0, c1, smem + OFF_G + (it & 1) * QTILE_BYTES, a_base, bT);   // dP - D = dO V^T - D
+      col_prefetch(y, smem + OFF_Q + slot * QTILE_BYTES, g_base);
+      __builtin_amdgcn_s_setprio(0);
+      lds_dma_wait();                            // this wavefront's copies into LDS have landed
+      DFA_BARRIER_NO_DRAIN();                    // nothing else it wrote has to be seen by the others
       slot = next;
     }
     dS_prev(niter);
-    col_products(acc, smem + OFF_Q + (slot == 0 ? 2 : slot - 1) * QTILE_BYTES, g_base, w);
+    col_products<true>(acc, smem + OFF_Q + (slot == 0 ? 2 : slot - 1) * QTILE_BYTES, g_base, w, y);
     __syncthreads();
   }
 
-#undef DFA_STAGE
 
   if (kvalid) {
     float* dst = (dp_wave ? p.dk : p.dv) + kh * p.dkv_sh + static_cast<int64_t>(kvrow) * p.dkv_ss;
@@ -563,13 +638,16 @@ int launch_bwd_bf16(const dfa_shape& sh, const void* q, const void* k, const voi
     const size_t smem = kv::SMEM_BYTES;
     static bool attr_set = false;   // > 64 KB of dynamic LDS needs the opt-in once per process
     if (!attr_set) {
-      const int rc = hip_status(hipFuncSetAttribute(reinterpret_cast<const void*>(kv::k_bwd_dkdv_bf16),
-                                                    hipFuncAttributeMaxDynamicSharedMemorySize,
-                                                    static_cast<int>(smem)));
-      if (rc) return rc;
+      for (const void* f : {reinterpret_cast<const void*>(kv::k_bwd_dkdv_bf16<false>),
+                            reinterpret_cast<const void*>(kv::k_bwd_dkdv_bf16<true>)}) {
+        const int rc = hip_status(hipFuncSetAttribute(f, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                                      static_cast<int>(smem)));
+        if (rc) return rc;
+      }
       attr_set = true;
     }
-    kv::k_bwd_dkdv_bf16<<<a.per_xcd * 8, kv::NT, smem, st>>>(a);
+    if (sh.s_q % kv::BM == 0) kv::k_bwd_dkdv_bf16<false><<<a.per_xcd * 8, kv::NT, smem, st>>>(a);
+    else kv::k_bwd_dkdv_bf16<true><<<a.per_xcd * 8, kv::NT, smem, st>>>(a);
     const int rc = last_launch_status();
     if (rc) return rc;
   }

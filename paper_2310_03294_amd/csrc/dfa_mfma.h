@@ -28,6 +28,7 @@ typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
 typedef short s16x4 __attribute__((ext_vector_type(4)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));   // an operand piece as raw bits (for values carried around a loop)
 
 #define DFA_LDS __attribute__((address_space(3)))
 
@@ -40,6 +41,12 @@ __device__ __forceinline__ f32x16 mfma32(bf16x8 a, bf16x8 b, f32x16 c) {
 // hardware needs there, which gave wrong results; the builtin above is the only form used.)
 
 #define DFA_SCHED_FENCE() __builtin_amdgcn_sched_barrier(0)
+// Workgroup barrier without the wait for this wavefront's outstanding memory operations that
+// __syncthreads() puts in front of it.  For a wavefront that only READS shared tiles and whose
+// reads still in flight target registers it consumes later (the compiler's own counters cover
+// those): nothing it wrote has to be visible to the others.  The "memory" clobber keeps the
+// compiler from moving memory accesses across it.
+#define DFA_BARRIER_NO_DRAIN() asm volatile("s_barrier" ::: "memory")
 
 constexpr int kRowBytes = 272;
 
@@ -157,6 +164,62 @@ __device__ __forceinline__ void tile_dma(const char* gbase, uint32_t rowbytes, i
     lds_dma16x4(g3, v[0], v[1], v[2], v[3], base + w * 4096);
     if (w == 0) lds_dma16(g3, v[4], base + 16 * 1024);
   }
+}
+
+// One wavefront's share of a tile copy (pieces 4w .. 4w + 3, and piece 16 for w == 0), resolved
+// to a scalar base and per-lane offsets, so that the pieces can be issued one at a time between
+// other instructions: the memory pipe takes about 17 cycles per 1 KB piece and CU, and a
+// wavefront that issues its pieces in a burst stalls until the pipe has taken them all.
+struct TileCopy {
+  const char* g;        // scalar base (taken 3072 bytes early, see TileLane)
+  uint32_t v[5];        // per-lane byte offsets of the five pieces
+  uint32_t lds, lds16;  // LDS addresses of piece 4w and of piece 16
+};
+
+// RAGGED false: the caller guarantees that every tile lies wholly inside the matrix.
+template <bool RAGGED = true>
+__device__ __forceinline__ TileCopy tile_copy_plan(const char* gbase, uint32_t rowbytes, int row0, int last,
+                                                   const TileLane& m, const char* tile, int w, int lane) {
+  TileCopy c;
+  const uint32_t base = lds_addr(tile);
+  c.lds = base + w * 4096;
+  c.lds16 = base + 16 * 1024;
+  const char* g3 = gbase - 3072;
+  if (!RAGGED || row0 + 63 <= last) {              // tile inside the matrix: its position goes into the scalar base
+    c.g = g3 + static_cast<uint64_t>(static_cast<uint32_t>(row0)) * rowbytes;
+#pragma unroll
+    for (int j = 0; j < 5; ++j) c.v[j] = m.voff[j];
+  } else {                                         // rows past `last` are clamped to it
+    c.g = g3;
+#pragma unroll
+    for (int j = 0; j < 5; ++j) {
+      int row; uint32_t cb;
+      tile_lane_rc(w, lane, j, row, cb);
+      const int r = row0 + row;
+      c.v[j] = static_cast<uint32_t>(r < last ? r : last) * rowbytes + cb + (j < 4 ? 3072 - 1024 * j : 3072);
+    }
+  }
+  return c;
+}
+
+// Piece J of the plan: J = 0..3 are pieces 4w + J, J = 4 is piece 16 (issue it from one wavefront only).
+template <int J>
+__device__ __forceinline__ void tile_copy_piece(const TileCopy& c) {
+  if constexpr (J == 0)
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
+                 :: "s"(c.lds), "v"(c.v[0]), "s"(c.g) : "memory", "m0");
+  else if constexpr (J == 1)
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2 offset:1024"
+                 :: "s"(c.lds), "v"(c.v[1]), "s"(c.g) : "memory", "m0");
+  else if constexpr (J == 2)
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2 offset:2048"
+                 :: "s"(c.lds), "v"(c.v[2]), "s"(c.g) : "memory", "m0");
+  else if constexpr (J == 3)
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2 offset:3072"
+                 :: "s"(c.lds), "v"(c.v[3]), "s"(c.g) : "memory", "m0");
+  else
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
+                 :: "s"(c.lds16), "v"(c.v[4]), "s"(c.g) : "memory", "m0");
 }
 
 __device__ __forceinline__ void lds_dma_wait() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
