@@ -528,13 +528,21 @@ __global__ void __launch_bounds__(NTHREADS, 2) k_bwd_dq_bf16(BwdParams p) {
     const int k0 = it * BN;
     const char* Ks = smem + (it & 1) * 2 * TILE_BYTES;
     const char* Vs = Ks + TILE_BYTES;
-    if (it + 1 < ntiles) {
-      const char* Kn = smem + ((it + 1) & 1) * 2 * TILE_BYTES;
-      tile_dma(kg, kv_rowbytes, k0 + BN, p.s_k - 1, tl, Kn, wave, lane);
-      tile_dma(vg, kv_rowbytes, k0 + BN, p.s_k - 1, tl, Kn + TILE_BYTES, wave, lane);
-    }
+    // The next K and V tiles into the other buffer, their pieces spread between the MFMAs below
+    // (issued in a burst they stall the wavefront while the memory pipe takes them in).  After the
+    // last tile the same tile goes once more into the idle buffer, which keeps the loop free of
+    // branches around the copies.
+    const int kn0 = it + 1 < ntiles ? k0 + BN : k0;
+    const char* Kn = smem + ((it + 1) & 1) * 2 * TILE_BYTES;
+    const TileCopy ck = tile_copy_plan(kg, kv_rowbytes, kn0, p.s_k - 1, tl, Kn, wave, lane);
+    const TileCopy cv = tile_copy_plan(vg, kv_rowbytes, kn0, p.s_k - 1, tl, Kn + TILE_BYTES, wave, lane);
 
     const bool active = !(p.causal && k0 > q0w + 31);
+    if (!active) {      // nothing to compute for this wavefront's rows: only its share of the copies
+      tile_copy_piece<0>(ck); tile_copy_piece<1>(ck); tile_copy_piece<2>(ck); tile_copy_piece<3>(ck);
+      tile_copy_piece<0>(cv); tile_copy_piece<1>(cv); tile_copy_piece<2>(cv); tile_copy_piece<3>(cv);
+      if (wave == 0) { tile_copy_piece<4>(ck); tile_copy_piece<4>(cv); }
+    }
     if (active) {
       const bool need_mask = (k0 + BN > p.s_k) || (p.causal && k0 + BN - 1 > q0w);
 #pragma unroll
@@ -555,6 +563,13 @@ __global__ void __launch_bounds__(NTHREADS, 2) k_bwd_dq_bf16(BwdParams p) {
         for (int ks = 0; ks < 8; ++ks) {
           s = mfma32(ka[ks & 3], qB[ks], s);
           dp = mfma32(va[ks & 3], gB[ks], ks == 0 ? negD : dp);      // the chain starts from -D
+          {   // one piece of the next tiles every other step: K under the first 32 keys, V under the second
+            const TileCopy& c = nb == 0 ? ck : cv;
+            if (ks == 0) tile_copy_piece<0>(c);
+            if (ks == 2) tile_copy_piece<1>(c);
+            if (ks == 4) tile_copy_piece<2>(c);
+            if (ks == 6) tile_copy_piece<3>(c);
+          }
           if (ks < 4) {
             const int off = a_base + nb * 32 * kRowBytes + (ks + 4) * 32;
             ka[ks & 3] = lds_read_b128(Ks, off);
@@ -575,6 +590,7 @@ __global__ void __launch_bounds__(NTHREADS, 2) k_bwd_dq_bf16(BwdParams p) {
             if (kvi >= p.s_k || (p.causal && kvi > qrow)) dp[j] = 0.f;
           }
         }
+        if (wave == 0) tile_copy_piece<4>(nb == 0 ? ck : cv);
         // dQ^T += K^T dS^T: 2 contraction steps of 16 keys, 4 blocks of 32 columns
         bf16x8 sb[2], gk[2];
         sb[0] = pack8(dp, 0); sb[1] = pack8(dp, 8);

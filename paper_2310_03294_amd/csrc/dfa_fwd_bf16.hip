@@ -168,13 +168,21 @@ __global__ void __launch_bounds__(NTHREADS, 2) k_fwd_bf16(FwdParams p) {
     const int boff = (it & 1) * 2 * TILE_BYTES;
     const char* Ks = smem + boff;
     const char* Vs = Ks + TILE_BYTES;
-    if (more) {
-      const char* Kn = smem + (2 * TILE_BYTES - boff);
-      tile_dma(kg, kv_rowbytes, k0 + BN, p.s_k - 1, tl, Kn, wave, lane);
-      tile_dma(vg, kv_rowbytes, k0 + BN, p.s_k - 1, tl, Kn + TILE_BYTES, wave, lane);
-    }
+    // The next K and V tiles into the other buffer, their pieces issued one at a time between the
+    // MFMAs of stages 1 and 4 (in a burst they stall the wavefront while the memory pipe takes them
+    // in).  After the last tile the same tile goes once more into the idle buffer: no branch
+    // around the copies.
+    const char* Kn = smem + (2 * TILE_BYTES - boff);
+    const int kn0 = more ? k0 + BN : k0;
+    const TileCopy ck = tile_copy_plan(kg, kv_rowbytes, kn0, p.s_k - 1, tl, Kn, wave, lane);
+    const TileCopy cv = tile_copy_plan(vg, kv_rowbytes, kn0, p.s_k - 1, tl, Kn + TILE_BYTES, wave, lane);
 
     const bool active = !(p.causal && k0 > q0w + 31);
+    if (!active) {      // nothing to compute for this wavefront's rows: only its share of the copies
+      tile_copy_piece<0>(ck); tile_copy_piece<1>(ck); tile_copy_piece<2>(ck); tile_copy_piece<3>(ck);
+      tile_copy_piece<0>(cv); tile_copy_piece<1>(cv); tile_copy_piece<2>(cv); tile_copy_piece<3>(cv);
+      if (wave == 0) { tile_copy_piece<4>(ck); tile_copy_piece<4>(cv); }
+    }
     if (active) {
       const bool need_mask = (k0 + BN > p.s_k) || (p.causal && k0 + BN - 1 > q0w);
       // Software pipeline over the two 32-key blocks of the tile: the MFMAs of one block run
@@ -191,8 +199,13 @@ __global__ void __launch_bounds__(NTHREADS, 2) k_fwd_bf16(FwdParams p) {
       for (int ks = 0; ks < 8; ++ks) {
         s0 = mfma32(ka[ks & 3], qreg[ks], s0);
         ka[ks & 3] = lds_read_b128(Ks, ks < 4 ? a_base + (ks + 4) * 32 : a_base + 32 * kRowBytes + (ks - 4) * 32);
+        if (ks == 0) tile_copy_piece<0>(ck);
+        if (ks == 2) tile_copy_piece<1>(ck);
+        if (ks == 4) tile_copy_piece<2>(ck);
+        if (ks == 6) tile_copy_piece<3>(ck);
         DFA_SCHED_FENCE();
       }
+      if (wave == 0) { tile_copy_piece<4>(ck); tile_copy_piece<4>(cv); }
       if (need_mask) mask_block(s0, k0);
       DFA_SCHED_FENCE();
       // stage 2: S1^T = K1 Q^T  ||  softmax of block 0
@@ -247,6 +260,10 @@ __global__ void __launch_bounds__(NTHREADS, 2) k_fwd_bf16(FwdParams p) {
           const int n = i + 10;
           gv[i & 1] = lds_gather(Vs, g_base + (n >> 2) * 16 * kRowBytes + (n & 3) * 64);
         }
+        if (i == 0) tile_copy_piece<0>(cv);
+        if (i == 2) tile_copy_piece<1>(cv);
+        if (i == 4) tile_copy_piece<2>(cv);
+        if (i == 6) tile_copy_piece<3>(cv);
         DFA_SCHED_FENCE();
       }
     }
@@ -308,6 +325,8 @@ constexpr int OFF_AL = OFF_PX + 2 * PX_BYTES;
 constexpr int OFF_ST = OFF_AL + 2 * AL_BYTES;  // 1 / row sum, written once by the S wavefronts
 constexpr int SMEM_BYTES = OFF_ST + AL_BYTES;
 
+// RAGGED: s_k is no multiple of the 64-row tile, so the last K/V tile has rows past the end.
+template <bool RAGGED>
 __global__ void __launch_bounds__(NT, 1) k_fwd_bf16(FwdParams p) {
   extern __shared__ __align__(16) char smem[];
 
@@ -366,12 +385,19 @@ __global__ void __launch_bounds__(NT, 1) k_fwd_bf16(FwdParams p) {
     for (int it = 0; it < ntiles; ++it) {
       const int k0 = it * BN;
       const char* Ks = smem + OFF_K + (it & 1) * TILE_BYTES;
-      if (it + 1 < ntiles) {
-        tile_dma(cg, kv_rowbytes, k0 + BN, last, tl,
-                 wave < 4 ? smem + OFF_K + ((it + 1) & 1) * TILE_BYTES : smem + OFF_V + ((it + 1) % 3) * TILE_BYTES,
-                 wave & 3, lane);
+      // This wavefront's pieces of the next K (or V) tile, issued one at a time between the MFMAs
+      // below: in a burst they would stall it while the memory pipe takes them in.  After the last
+      // tile the same tile goes once more into a ring slot nobody reads (no branch around the copies).
+      const TileCopy cn = tile_copy_plan<RAGGED>(cg, kv_rowbytes, it + 1 < ntiles ? k0 + BN : k0, last, tl,
+                                         wave < 4 ? smem + OFF_K + ((it + 1) & 1) * TILE_BYTES
+                                                  : smem + OFF_V + ((it + 1) % 3) * TILE_BYTES,
+                                         wave & 3, lane);
+      const bool active = !(p.causal && k0 > q0w + 31);   // else: the whole tile lies above this block's diagonal
+      if (!active) {
+        tile_copy_piece<0>(cn); tile_copy_piece<1>(cn); tile_copy_piece<2>(cn); tile_copy_piece<3>(cn);
+        if ((wave & 3) == 0) tile_copy_piece<4>(cn);
       }
-      if (!(p.causal && k0 > q0w + 31)) {    // else: the whole tile lies above this block's diagonal
+      if (active) {
         f32x16 s0, s1;
         {
           bf16x8 x0[4], x1[4];
@@ -384,6 +410,7 @@ __global__ void __launch_bounds__(NT, 1) k_fwd_bf16(FwdParams p) {
             x1[ks] = lds_read_b128(Ks, a_base + 32 * kRowBytes + ks * 32);
           }
           DFA_SCHED_FENCE();
+          __builtin_amdgcn_s_setprio(3);         // MFMAs first: the other wavefronts' VALU work fills the gaps
 #pragma unroll
           for (int ks = 0; ks < 8; ++ks) {
             if (ks + 3 < 8) {
@@ -392,8 +419,14 @@ __global__ void __launch_bounds__(NT, 1) k_fwd_bf16(FwdParams p) {
             }
             s0 = mfma32(x0[ks & 3], qreg[ks], ks == 0 ? zero : s0);
             s1 = mfma32(x1[ks & 3], qreg[ks], ks == 0 ? zero : s1);
+            if (ks == 0) tile_copy_piece<0>(cn);
+            if (ks == 2) tile_copy_piece<1>(cn);
+            if (ks == 4) tile_copy_piece<2>(cn);
+            if (ks == 6) tile_copy_piece<3>(cn);
             DFA_SCHED_FENCE();
           }
+          __builtin_amdgcn_s_setprio(0);
+          if ((wave & 3) == 0) tile_copy_piece<4>(cn);
         }
         if ((k0 + BN > p.s_k) || (p.causal && k0 + BN - 1 > q0w)) {
 #pragma unroll
@@ -499,12 +532,14 @@ __global__ void __launch_bounds__(NT, 1) k_fwd_bf16(FwdParams p) {
           for (int j = 0; j < 16; ++j) o[i][j] *= a;
       }
       DFA_SCHED_FENCE();
+      __builtin_amdgcn_s_setprio(3);
 #pragma unroll
       for (int n = 0; n < 16; ++n) {
         if (n + AHEAD < 16) y[(n + AHEAD) % (AHEAD + 1)] = lds_gather(Vs, voff(n + AHEAD));
         o[n & 3] = mfma32(y[n % (AHEAD + 1)], pa[n >> 2], o[n & 3]);
         DFA_SCHED_FENCE();
       }
+      __builtin_amdgcn_s_setprio(0);
     };
 
     __syncthreads();                         // tile 0 is in LDS
@@ -556,12 +591,18 @@ int launch_fwd_bf16(const dfa_shape& sh, const void* q, const void* k, const voi
     p.per_xcd = (p.total + 7) / 8;
     static bool attr2 = false;
     if (!attr2) {
-      const int rc = hip_status(hipFuncSetAttribute(reinterpret_cast<const void*>(full_pair::k_fwd_bf16),
-                                                    hipFuncAttributeMaxDynamicSharedMemorySize, full_pair::SMEM_BYTES));
-      if (rc) return rc;
+      for (const void* f : {reinterpret_cast<const void*>(full_pair::k_fwd_bf16<false>),
+                            reinterpret_cast<const void*>(full_pair::k_fwd_bf16<true>)}) {
+        const int rc = hip_status(hipFuncSetAttribute(f, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                                      full_pair::SMEM_BYTES));
+        if (rc) return rc;
+      }
       attr2 = true;
     }
-    full_pair::k_fwd_bf16<<<p.per_xcd * 8, full_pair::NT, full_pair::SMEM_BYTES, st>>>(p);
+    if (sh.s_k % BN == 0)
+      full_pair::k_fwd_bf16<false><<<p.per_xcd * 8, full_pair::NT, full_pair::SMEM_BYTES, st>>>(p);
+    else
+      full_pair::k_fwd_bf16<true><<<p.per_xcd * 8, full_pair::NT, full_pair::SMEM_BYTES, st>>>(p);
     return last_launch_status();
   }
   p.ntq = (sh.s_q + BM - 1) / BM;
