@@ -461,12 +461,13 @@ __global__ void __launch_bounds__(NT, 1) k_fwd_bf16(FwdParams p) {
           sum += s0[j] + s1[j];
         }
         l_run += sum;
+        const bf16x8 p0 = pack8(s0, 0), p1 = pack8(s0, 8), p2 = pack8(s1, 0), p3 = pack8(s1, 8);
         // hand P^T and the factor to the PV wavefront: lane-private, any layout will do
         char* px = smem + OFF_PX + (it & 1) * PX_BYTES + wave * 4096 + lane * 16;
-        *reinterpret_cast<bf16x8*>(px) = pack8(s0, 0);
-        *reinterpret_cast<bf16x8*>(px + 1024) = pack8(s0, 8);
-        *reinterpret_cast<bf16x8*>(px + 2048) = pack8(s1, 0);
-        *reinterpret_cast<bf16x8*>(px + 3072) = pack8(s1, 8);
+        *reinterpret_cast<bf16x8*>(px) = p0;
+        *reinterpret_cast<bf16x8*>(px + 1024) = p1;
+        *reinterpret_cast<bf16x8*>(px + 2048) = p2;
+        *reinterpret_cast<bf16x8*>(px + 3072) = p3;
         if (hh == 0) al[(it & 1) * (AL_BYTES / 4)] = alpha;
       }
       lds_dma_wait();
@@ -517,14 +518,15 @@ __global__ void __launch_bounds__(NT, 1) k_fwd_bf16(FwdParams p) {
       const char* px = smem + OFF_PX + (t & 1) * PX_BYTES + sw * 4096 + lane * 16;
       const float a = reinterpret_cast<const float*>(smem + OFF_AL)[(t & 1) * (AL_BYTES / 4) + sw * 32 + r32];
       constexpr int AHEAD = 6;               // V^T gathers run this many steps ahead of their MFMAs
+      const uint32_t vb = lds_pin(lds_addr(Vs) + g_base);
       auto voff = [&](int n) {               // n = key block * 8 + half * 4 + d block
-        return g_base + ((n >> 3) * 32 + ((n >> 2) & 1) * 16) * kRowBytes + (n & 3) * 64;
+        return ((n >> 3) * 32 + ((n >> 2) & 1) * 16) * kRowBytes + (n & 3) * 64;
       };
       bf16x8 y[AHEAD + 1], pa[4];
 #pragma unroll
       for (int j = 0; j < 4; ++j) pa[j] = *reinterpret_cast<const bf16x8*>(px + j * 1024);
 #pragma unroll
-      for (int n = 0; n < AHEAD; ++n) y[n] = lds_gather(Vs, voff(n));
+      for (int n = 0; n < AHEAD; ++n) y[n] = lds_gather_at(vb, voff(n));
       if (__any(a != 1.f)) {
 #pragma unroll
         for (int i = 0; i < 4; ++i)
@@ -535,7 +537,7 @@ __global__ void __launch_bounds__(NT, 1) k_fwd_bf16(FwdParams p) {
       __builtin_amdgcn_s_setprio(3);
 #pragma unroll
       for (int n = 0; n < 16; ++n) {
-        if (n + AHEAD < 16) y[(n + AHEAD) % (AHEAD + 1)] = lds_gather(Vs, voff(n + AHEAD));
+        if (n + AHEAD < 16) y[(n + AHEAD) % (AHEAD + 1)] = lds_gather_at(vb, voff(n + AHEAD));
         o[n & 3] = mfma32(y[n % (AHEAD + 1)], pa[n >> 2], o[n & 3]);
         DFA_SCHED_FENCE();
       }

@@ -78,6 +78,25 @@ __device__ __forceinline__ int gather_base(int lane) {
   return tile_off(4 * (g >> 1) + (j >> 2), 2 * (g & 1) + ((j & 3) >> 1)) + ((j & 1) << 3);
 }
 
+// The same from a 32-bit LDS address held in a register that the compiler must take as it is
+// (see lds_pin): the constant part of every read then goes into the instruction's offset field.
+__device__ __forceinline__ bf16x4 lds_read_tr_at(uint32_t addr, int off) {
+  s16x4 v = __builtin_amdgcn_ds_read_tr16_b64_v4i16((DFA_LDS s16x4*)(addr + off));
+  return __builtin_bit_cast(bf16x4, v);
+}
+__device__ __forceinline__ bf16x8 lds_gather_at(uint32_t addr, int off) {
+  const bf16x4 lo = lds_read_tr_at(addr, off);
+  const bf16x4 hi = lds_read_tr_at(addr, off + 2 * kRowBytes);
+  return __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+}
+// Makes `addr` opaque to the compiler, so that it stays THE base register of the reads that
+// follow.  Left alone, the compiler may pick a base above them and spend one v_add per read on
+// the (negative, not encodable) differences.
+__device__ __forceinline__ uint32_t lds_pin(uint32_t addr) {
+  asm volatile("" : "+v"(addr));
+  return addr;
+}
+
 __device__ __forceinline__ bf16x8 lds_gather(const char* base, int off) {
   const bf16x4 lo = lds_read_tr(base, off);
   const bf16x4 hi = lds_read_tr(base, off + 2 * kRowBytes);   // logical rows +8 = physical rows +2

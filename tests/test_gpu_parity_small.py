@@ -57,6 +57,7 @@ SHAPES_BF16 = [
     (2, 2, 128, 128, 128, True), (2, 2, 256, 192, 128, False), (4, 2, 384, 384, 128, True),
     (3, 1, 100, 77, 128, False), (2, 1, 1, 1, 128, True), (2, 2, 65, 191, 128, False), (8, 2, 257, 257, 128, True),
     (1, 1, 1024, 1024, 128, True), (2, 1, 640, 1152, 128, False),
+    (4, 2, 333, 451, 128, False), (4, 2, 333, 333, 128, True),      # several tiles, ragged ends on both axes, grouped heads
 ]
 
 
