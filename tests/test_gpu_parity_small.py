@@ -355,3 +355,28 @@ def test_mfma_probe_runs_and_counts_its_flop():
     torch.cuda.synchronize()
     assert flop == 2.0 * 32 * 32 * 16 * 4 * 100 * 2048
     assert bool(torch.isfinite(out).all())
+
+
+@pytest.mark.parametrize("shape", [(4, 2, 333, 451, False, 12), (8, 2, 257, 257, True, 12), (32, 8, 1024, 2048, False, 6)])
+def test_results_repeat_bit_for_bit(shape):
+    """The kernels use no atomics and a fixed summation order, so repeated calls must agree bit for
+    bit; a difference would point at a missing wait or barrier between the tile copies, the
+    hand-over buffers and their readers (the last shape fills every compute unit)."""
+    h_q, h_kv, s_q, s_k, causal, reps = shape
+    d = 128
+    q, k, v, do = case(4242 + s_q, h_q, h_kv, s_q, s_k, d, torch.bfloat16)
+    Q, K, V, dO = (t.to(dev()) for t in (q, k, v, do))
+    scale = 1 / math.sqrt(d)
+    first = None
+    for _ in range(reps):
+        o, lse = dfa.dfa_chunk_fwd(Q, K, V, causal, scale)
+        delta = dfa.dfa_delta(o, dO)
+        dq = torch.empty(h_q, s_q, d, device=dev()); dk = torch.empty(h_kv, s_k, d, device=dev())
+        dv = torch.empty(h_kv, s_k, d, device=dev())
+        dfa.dfa_chunk_bwd(Q, K, V, lse, delta, dO, dq, dk, dv, causal, scale, accumulate=False)
+        torch.cuda.synchronize()
+        cur = (o, lse, delta, dq, dk, dv)
+        if first is None:
+            first = cur
+        else:
+            assert all(torch.equal(a, b) for a, b in zip(first, cur))
