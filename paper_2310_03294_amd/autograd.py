@@ -23,9 +23,15 @@ from . import driver
 # pairs computed by dfa_chunk_fwd / dfa_chunk_fwd_acc since the last reset (for tests and for
 # showing what each checkpoint placement re-runs)
 forward_pair_calls = 0
+# When set, every backward leaves its gradients here as the library produced them (fp32 dq, dk, dv),
+# before they are rounded to the dtype of the inputs they are handed to.
+keep_fp32_grads = False
+last_fp32_grads = None
 
 
 def _forward(q, k, v, scale, P):
+    """Runs the whole balanced schedule; returns the merged output and logsumexp, both fp32 (the
+    state the schedule carries and the backward reuses; callers get the output in q's dtype)."""
     global forward_pair_calls
     h_q, n, d = q.shape
     bufs = driver.Buffers(h_q, k.shape[0], n, d, P, q.device, grads=False)
@@ -35,14 +41,15 @@ def _forward(q, k, v, scale, P):
 
 
 class DistFlashAttnFunction(torch.autograd.Function):
-    """o = causal_attention(q, k, v) for [heads, N, d] bf16 / fp32 tensors, N divisible by P."""
+    """o = causal_attention(q, k, v) for [heads, N, d] bf16 / fp32 tensors, N divisible by P.
+    o has q's dtype; what is saved for the backward is the fp32 output and its logsumexp."""
 
     @staticmethod
     def forward(ctx, q, k, v, scale, P):
         o, lse = _forward(q, k, v, scale, P)
         ctx.save_for_backward(q, k, v, o, lse)
         ctx.scale, ctx.P = scale, P
-        return o
+        return o.to(q.dtype)
 
     @staticmethod
     def backward(ctx, d_o):
@@ -51,16 +58,22 @@ class DistFlashAttnFunction(torch.autograd.Function):
 
 
 def _backward(q, k, v, o, lse, d_o, scale, P):
+    """Gradients from the saved (q, k, v, O, logsumexp) and dO, which is rounded to the dtype of q
+    (the kernels read dO in the inputs' dtype).  The library's gradients are fp32; autograd hands a
+    tensor gradients of its own dtype, so they are rounded to it on return."""
+    global last_fp32_grads
     h_q, n, d = q.shape
     c = n // P
     d_o = d_o.to(q.dtype).contiguous()
-    bufs = driver.Buffers(h_q, k.shape[0], n, d, P, q.device, grads=True)
+    bufs = driver.Buffers(h_q, k.shape[0], n, d, P, q.device, grads=True, outputs=False)
     bufs.O, bufs.L = o, lse
     for w in range(P):
         B.dfa_delta(o[:, w * c:(w + 1) * c], d_o[:, w * c:(w + 1) * c], delta=bufs.delta[:, w * c:(w + 1) * c])
     touched = driver.new_pass()
     for w in range(P):
         driver.backward_worker(q, k, v, d_o, scale, P, w, bufs, with_delta=False, touched=touched)
+    if keep_fp32_grads:
+        last_fp32_grads = (bufs.dQ, bufs.dK, bufs.dV)
     return bufs.dQ.to(q.dtype), bufs.dK.to(k.dtype), bufs.dV.to(v.dtype)
 
 
@@ -75,7 +88,7 @@ class _BlockFunction(torch.autograd.Function):
     def forward(ctx, q, k, v, scale, P, f, placement):
         o, lse = _forward(q, k, v, scale, P)
         with torch.no_grad():
-            y = f(o)
+            y = f(o.to(q.dtype))
         if placement == "attention_output":
             ctx.save_for_backward(q, k, v, o, lse)        # the checkpoint is the attention output
         else:
@@ -91,7 +104,7 @@ class _BlockFunction(torch.autograd.Function):
             q, k, v = ctx.saved_tensors
             o, lse = _forward(q, k, v, ctx.scale, ctx.P)   # recomputation re-runs the attention forward
         with torch.enable_grad():
-            o_in = o.detach().requires_grad_(True)
+            o_in = o.detach().to(q.dtype).requires_grad_(True)
             y = ctx.f(o_in)                                # recompute f only
         (d_o,) = torch.autograd.grad(y, o_in, d_y)
         return (*_backward(q, k, v, o, lse, d_o, ctx.scale, ctx.P), None, None, None, None)
@@ -127,7 +140,6 @@ def _main():
     dev = torch.device("cuda:0")
     q, k, v, d_y = (dfa_inputs.full_sequence(w, t).to(dev) for t in range(4))
     q.requires_grad_(True); k.requires_grad_(True); v.requires_grad_(True)
-    d_y = d_y.float()
     out = {"workload": w.name, "P": w.p, "steps": args.steps}
     for placement in ("attention_output", "layer_boundary"):
         block = CheckpointedBlock(lambda o: o, w.scale, w.p, placement)

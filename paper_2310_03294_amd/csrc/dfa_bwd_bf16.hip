@@ -27,6 +27,8 @@
 // retire about one fp32 atomic per clock and channel (~3.1e11 per second on the whole chip),
 // which caps a 128-key workgroup tile at ~400 TFLOP/s no matter how the rest is scheduled.
 // Recomputing S and dP in a second kernel costs 7 products instead of 5 but has no such cap.
+#include <mutex>
+
 #include "dfa_internal.h"
 #include "dfa_mfma.h"
 
@@ -652,16 +654,18 @@ int launch_bwd_bf16(const dfa_shape& sh, const void* q, const void* k, const voi
     a.total = static_cast<int>(total);
     a.per_xcd = (a.total + 7) / 8;
     const size_t smem = kv::SMEM_BYTES;
-    static bool attr_set = false;   // > 64 KB of dynamic LDS needs the opt-in once per process
-    if (!attr_set) {
+    // > 64 KB of dynamic LDS needs the opt-in, once per process (thread-safe)
+    static std::once_flag once;
+    static int attr_rc = DFA_OK;
+    std::call_once(once, [smem] {
       for (const void* f : {reinterpret_cast<const void*>(kv::k_bwd_dkdv_bf16<false>),
                             reinterpret_cast<const void*>(kv::k_bwd_dkdv_bf16<true>)}) {
         const int rc = hip_status(hipFuncSetAttribute(f, hipFuncAttributeMaxDynamicSharedMemorySize,
                                                       static_cast<int>(smem)));
-        if (rc) return rc;
+        if (rc) attr_rc = rc;
       }
-      attr_set = true;
-    }
+    });
+    if (attr_rc) return attr_rc;
     if (sh.s_q % kv::BM == 0) kv::k_bwd_dkdv_bf16<false><<<a.per_xcd * 8, kv::NT, smem, st>>>(a);
     else kv::k_bwd_dkdv_bf16<true><<<a.per_xcd * 8, kv::NT, smem, st>>>(a);
     const int rc = last_launch_status();
@@ -675,14 +679,14 @@ int launch_bwd_bf16(const dfa_shape& sh, const void* q, const void* k, const voi
     b.total = static_cast<int>(total);
     b.per_xcd = (b.total + 7) / 8;
     const size_t smem = 4 * qs::TILE_BYTES;
-    static bool attr_set = false;
-    if (!attr_set) {
-      const int rc = hip_status(hipFuncSetAttribute(reinterpret_cast<const void*>(qs::k_bwd_dq_bf16),
-                                                    hipFuncAttributeMaxDynamicSharedMemorySize,
-                                                    static_cast<int>(smem)));
-      if (rc) return rc;
-      attr_set = true;
-    }
+    static std::once_flag once;
+    static int attr_rc = DFA_OK;
+    std::call_once(once, [smem] {
+      attr_rc = hip_status(hipFuncSetAttribute(reinterpret_cast<const void*>(qs::k_bwd_dq_bf16),
+                                               hipFuncAttributeMaxDynamicSharedMemorySize,
+                                               static_cast<int>(smem)));
+    });
+    if (attr_rc) return attr_rc;
     qs::k_bwd_dq_bf16<<<b.per_xcd * 8, NTHREADS, smem, st>>>(b);
   }
   return last_launch_status();

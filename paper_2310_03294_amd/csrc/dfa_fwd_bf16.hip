@@ -11,6 +11,8 @@
 // into LDS (double-buffered); K is read from LDS with ds_read_b128, V with the transposing
 // ds_read_b64_tr_b16.  The causal mask is applied only on tiles that straddle the
 // diagonal; tiles above it are skipped.
+#include <mutex>
+
 #include "dfa_internal.h"
 #include "dfa_mfma.h"
 
@@ -591,16 +593,18 @@ int launch_fwd_bf16(const dfa_shape& sh, const void* q, const void* k, const voi
     p.ntq = (sh.s_q + full_pair::BMW - 1) / full_pair::BMW;
     p.total = p.ntq * sh.h_q;
     p.per_xcd = (p.total + 7) / 8;
-    static bool attr2 = false;
-    if (!attr2) {
+    // > 64 KB of dynamic LDS needs the opt-in, once per process (thread-safe)
+    static std::once_flag once;
+    static int attr_rc = DFA_OK;
+    std::call_once(once, [] {
       for (const void* f : {reinterpret_cast<const void*>(full_pair::k_fwd_bf16<false>),
                             reinterpret_cast<const void*>(full_pair::k_fwd_bf16<true>)}) {
         const int rc = hip_status(hipFuncSetAttribute(f, hipFuncAttributeMaxDynamicSharedMemorySize,
                                                       full_pair::SMEM_BYTES));
-        if (rc) return rc;
+        if (rc) attr_rc = rc;
       }
-      attr2 = true;
-    }
+    });
+    if (attr_rc) return attr_rc;
     if (sh.s_k % BN == 0)
       full_pair::k_fwd_bf16<false><<<p.per_xcd * 8, full_pair::NT, full_pair::SMEM_BYTES, st>>>(p);
     else
@@ -613,13 +617,13 @@ int launch_fwd_bf16(const dfa_shape& sh, const void* q, const void* k, const voi
   p.total = static_cast<int>(total);
   p.per_xcd = (p.total + 7) / 8;
   const size_t smem = 4 * TILE_BYTES;     // two (K, V) buffers; above 64 KB needs the opt-in once
-  static bool attr_set = false;
-  if (!attr_set) {
-    const int rc = hip_status(hipFuncSetAttribute(reinterpret_cast<const void*>(k_fwd_bf16),
-                                                  hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(smem)));
-    if (rc) return rc;
-    attr_set = true;
-  }
+  static std::once_flag once;
+  static int attr_rc = DFA_OK;
+  std::call_once(once, [smem] {
+    attr_rc = hip_status(hipFuncSetAttribute(reinterpret_cast<const void*>(k_fwd_bf16),
+                                             hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(smem)));
+  });
+  if (attr_rc) return attr_rc;
   k_fwd_bf16<<<p.per_xcd * 8, NTHREADS, smem, st>>>(p);
   return last_launch_status();
 }

@@ -15,13 +15,14 @@ from . import binding as B
 class Buffers:
     """Device buffers for one run, allocated once so that timed regions allocate nothing."""
 
-    def __init__(self, h_q, h_kv, n, d, p, device, o_dtype=torch.float32, n_partials=1, grads=True):
+    def __init__(self, h_q, h_kv, n, d, p, device, o_dtype=torch.float32, n_partials=1, grads=True, outputs=True):
         c = n // p
         self.c, self.p = c, p
-        self.O = torch.empty((h_q, n, d), dtype=o_dtype, device=device)
-        self.L = torch.empty((h_q, n), dtype=torch.float32, device=device)
-        self.part_o = [torch.empty((h_q, c, d), dtype=o_dtype, device=device) for _ in range(n_partials)]
-        self.part_l = [torch.empty((h_q, c), dtype=torch.float32, device=device) for _ in range(n_partials)]
+        if outputs:     # False: the caller supplies O and L (a backward from saved tensors)
+            self.O = torch.empty((h_q, n, d), dtype=o_dtype, device=device)
+            self.L = torch.empty((h_q, n), dtype=torch.float32, device=device)
+            self.part_o = [torch.empty((h_q, c, d), dtype=o_dtype, device=device) for _ in range(n_partials)]
+            self.part_l = [torch.empty((h_q, c), dtype=torch.float32, device=device) for _ in range(n_partials)]
         if grads:
             self.delta = torch.empty((h_q, n), dtype=torch.float32, device=device)
             self.dQ = torch.zeros((h_q, n, d), dtype=torch.float32, device=device)

@@ -13,7 +13,7 @@ pytestmark = pytest.mark.gpu
 
 
 def _f(o):                      # the rest of the block: any differentiable function of the attention output
-    return torch.tanh(o) * 0.5 + o
+    return 0.5 * torch.tanh(o) + 0.5 * o        # slope in (0.5, 1]: dO is no larger than the dy fed in
 
 
 def _oracle(q, k, v, d_y, scale):
@@ -26,25 +26,39 @@ def _oracle(q, k, v, d_y, scale):
     return y.detach().numpy(), dq, dk, dv
 
 
-@pytest.mark.parametrize("dtype,d,tol", [(torch.float32, 64, 2e-5), (torch.bfloat16, 128, 6e-2)])
+@pytest.mark.parametrize("dtype,d,tol", [(torch.float32, 64, 1e-5), (torch.bfloat16, 128, 2e-2)])
 @pytest.mark.parametrize("placement", ["attention_output", "layer_boundary"])
 def test_checkpointed_block(dtype, d, tol, placement):
+    """Both checkpoint placements against the oracle at the stated tolerances (1e-5 fp32, 2e-2 bf16).
+    The gradients compared are the library's fp32 dq, dk, dv; what autograd stores in .grad of a
+    bf16 tensor is their rounding to bf16 (half an ulp of a gradient above 8 is already 0.03), which
+    is checked to be exactly that rounding."""
     from paper_2310_03294_amd import autograd as AG
     w = dfa_inputs.Workload("t_autograd", 4, 2, d, 512, 4, "f32" if dtype == torch.float32 else "bf16", 99)
     q, k, v, d_y = (dfa_inputs.full_sequence(w, t) for t in range(4))
     Q, K, V = (t.to(dev()).requires_grad_(True) for t in (q, k, v))
     block = AG.CheckpointedBlock(_f, w.scale, w.p, placement)
     AG.forward_pair_calls = 0
-    y = block(Q, K, V)
-    pairs = w.p * (w.p + 1) // 2
-    assert AG.forward_pair_calls == pairs
-    y.backward(d_y.to(dev()).to(y.dtype))
-    torch.cuda.synchronize()
+    AG.keep_fp32_grads = True
+    try:
+        y = block(Q, K, V)
+        assert y.dtype == dtype
+        pairs = w.p * (w.p + 1) // 2
+        assert AG.forward_pair_calls == pairs
+        y.backward(d_y.to(dev()).to(y.dtype))
+        torch.cuda.synchronize()
+        g32 = AG.last_fp32_grads
+    finally:
+        AG.keep_fp32_grads = False
+        AG.last_fp32_grads = None
     # the remat-aware placement re-runs no attention forward; the usual one re-runs all of it
     assert AG.forward_pair_calls == (pairs if placement == "attention_output" else 2 * pairs)
     ry, rq, rk, rv = _oracle(q, k, v, d_y, w.scale)
-    errs = dict(y=maxerr(y, ry), dq=maxerr(Q.grad, rq), dk=maxerr(K.grad, rk), dv=maxerr(V.grad, rv))
+    assert all(g.dtype == torch.float32 for g in g32)
+    errs = dict(y=maxerr(y, ry), dq=maxerr(g32[0], rq), dk=maxerr(g32[1], rk), dv=maxerr(g32[2], rv))
     assert all(e <= tol for e in errs.values()), errs
+    for leaf, g in zip((Q, K, V), g32):
+        assert leaf.grad.dtype == dtype and torch.equal(leaf.grad, g.to(dtype))
 
 
 def test_function_matches_oracle_fp32():

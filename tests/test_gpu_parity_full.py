@@ -7,6 +7,10 @@ checks (every expected value is an exact fp64 evaluation of the definition, neve
     dq_i, each against the row's full key range;
   * sampled key columns at the tail of the sequence (only the last T query rows attend to them,
     so their L_i, D_i are affordable): dk_j, dv_j, summed over the query heads of the group;
+  * sampled key columns of ONE full (unmasked) pair at chunk 16384 and 65536: dfa_chunk_bwd takes
+    the query rows' logsumexp and D as inputs, and so does the oracle's column sampler, so both
+    sides are handed the same caller-chosen vectors and dk_j, dv_j of any column cost
+    O(chunk x d) in fp64;
   * identities that hold at any size, evaluated in fp64 on the GPU outputs:
     <Q, dQ> = <K, dK> over any set of pairs, and, when every pair of the sequence is present
     (config 5), sum_j dV_j = sum_i dO_i per kv group and sum_j dK_j = 0.
@@ -226,3 +230,74 @@ def test_config5_gqa_all_workers_full_size():
     # n terms, each within ~2^-9 relative of its exact value, adding up like a random walk
     bound = math.sqrt(n) * 2.0 ** -9
     assert e_dv <= bound and e_dk <= bound, (e_dv, e_dk, bound)
+
+
+def _sample_cols(c, n_random, seed):
+    """Key columns of a chunk of c rows: both ends, the first and last 128-key workgroup tile's
+    edges, 32-key wavefront blocks and 128-key tiles +-1 at a few depths, and random columns."""
+    cols = {0, 1, 31, 32, 127, 128, c - 129, c - 128, c - 33, c - 32, c - 2, c - 1}
+    for base in (c // 4, c // 2, (3 * c) // 4):
+        b = (base // 128) * 128
+        cols |= {b - 1, b, b + 31, b + 32, b + 63, b + 64, b + 127}
+    rng = np.random.default_rng(seed)
+    cols |= set(int(x) for x in rng.integers(0, c, n_random))
+    return np.array(sorted(x for x in cols if 0 <= x < c))
+
+
+@pytest.mark.parametrize("c", [16384, 65536])
+def test_full_pair_dkdv_sampled_columns(c):
+    """dk_j, dv_j of one full pair (query chunk 1 against key/value chunk 0, 32 heads, d = 128) at the
+    chunk sizes of configurations 3 and 4, for ~200 key columns of three heads (the first, a middle
+    and the last one: both ends of the workgroup -> XCD range).  The logsumexp and D of the
+    query rows are inputs of the backward on both sides: lse_i = log c + scale^2 |q_i|^2 / 2 (what
+    i.i.d. N(0, 1) keys give in expectation, so P has its real magnitude) and D_i ~ N(0, 0.1)."""
+    w = dfa_inputs.Workload(f"t_pair_c{c}", 32, 32, 128, 2 * c, 2, "bf16", 4000 + c // 1024)
+    heads = [0, 13, 31]
+    d = dev()
+    t0 = time.time()
+    q = dfa_inputs.workload_chunk(w, dfa_inputs.TENSOR_Q, 1)
+    do = dfa_inputs.workload_chunk(w, dfa_inputs.TENSOR_DO, 1)
+    k = dfa_inputs.workload_chunk(w, dfa_inputs.TENSOR_K, 0)
+    v = dfa_inputs.workload_chunk(w, dfa_inputs.TENSOR_V, 0)
+    g = torch.Generator().manual_seed(w.seed)
+    delta = 0.1 * torch.randn(w.h_q, c, generator=g)
+    lse = math.log(c) + 0.5 * w.scale ** 2 * q.float().pow(2).sum(-1)
+    # operands are chunk slices of [heads, 2c, d] tensors, as when a schedule walks a sequence
+    def slot(t, i, dtype=torch.bfloat16, fill=0.0):
+        full = torch.full((t.shape[0], 2 * c) + tuple(t.shape[2:]), fill, dtype=dtype, device=d)
+        view = full[:, i * c:(i + 1) * c]
+        view.copy_(t.to(d))
+        return view
+
+    Q, dO, K, V = slot(q, 1), slot(do, 1), slot(k, 0), slot(v, 0)
+    LSE, DEL = slot(lse, 1, torch.float32), slot(delta, 1, torch.float32)
+    _log(f"{w.name}: inputs generated and uploaded in {time.time() - t0:.1f} s")
+    dkv_full = torch.full((2, w.h_kv, 2 * c, w.d), float("nan"), device=d)
+    dk, dv = dkv_full[0, :, :c], dkv_full[1, :, :c]
+    dfa.dfa_chunk_bwd(Q, K, V, LSE, DEL, dO, None, dk, dv, False, w.scale, accumulate=False)
+    torch.cuda.synchronize()
+    assert bool(torch.isnan(dkv_full[:, :, c:]).all())       # the neighbouring chunk's rows are untouched
+    assert not torch.isnan(dk).any() and not torch.isnan(dv).any()
+    cols = _sample_cols(c, 160, w.seed)
+    idx = torch.as_tensor(cols, device=d)
+    for h in heads:
+        # query rows are global rows c .. 2c-1, key columns 0 .. c-1: every key is visible
+        rk, rv = A.cols_dkdv(np64(k[h, cols]), np64(v[h, cols]), cols, np64(q[h]), np64(do[h]), np64(lse[h]),
+                             np64(delta[h]), w.scale, row_lo=c)
+        gk, gv = np64(dk[h, idx]), np64(dv[h, idx])
+        errs = dict(dk=np.abs(gk - rk).max(), dv=np.abs(gv - rv).max())
+        # the sums over 10^4..10^5 rows are small numbers: also bound every column's error relative
+        # to that column's largest expected element
+        rel = dict(dk=(np.abs(gk - rk).max(1) / np.maximum(np.abs(rk).max(1), 1e-3)).max(),
+                   dv=(np.abs(gv - rv).max(1) / np.maximum(np.abs(rv).max(1), 1e-3)).max())
+        _log(f"{w.name} head {h}: {len(cols)} key columns  " + "  ".join(f"{k_}={v_:.2e}" for k_, v_ in errs.items())
+             + "  column-relative " + "  ".join(f"{k_}={v_:.2e}" for k_, v_ in rel.items())
+             + f"  (largest expected |dk| {np.abs(rk).max():.3e}, |dv| {np.abs(rv).max():.3e})")
+        assert all(e <= TOL for e in errs.values()), errs
+        assert all(e <= REL_TOL for e in rel.values()), rel
+
+
+def test_config3_one_whole_head():
+    """Config 3 (chunk 16384): one whole head of worker 7's share element by element - o, lse, dq of
+    the chunk and dk, dv of all five key/value chunks the share touches (about a minute of fp64)."""
+    _run_share(dfa_inputs.CONFIGS[2], heads=[9], full_heads=[9], n_random=4, tail=128)

@@ -146,6 +146,55 @@ def test_delta_identity():
     assert np.abs(A.delta_rows(O, do) - (P * dP).sum(-1)).max() < 1e-13
 
 
+# ----------------------------------------------- unmasked rectangular pairs (s_q != s_k)
+@pytest.mark.parametrize("h_q,h_kv,s_q,s_k,d", [(3, 1, 23, 41, 8), (4, 2, 50, 17, 16), (2, 2, 1, 9, 4)])
+def test_unmasked_rectangular_pair_matches_torch(h_q, h_kv, s_q, s_k, d):
+    """causal=False with different numbers of query and key rows (a query chunk against an earlier,
+    ragged key/value chunk): forward against torch's fp64 softmax / logsumexp, backward against
+    torch autograd; grouped heads sum into their key/value head."""
+    g = torch.Generator().manual_seed(31 + s_q)
+    tq = torch.randn(h_q, s_q, d, generator=g, dtype=torch.float64, requires_grad=True)
+    tdo = torch.randn(h_q, s_q, d, generator=g, dtype=torch.float64)
+    tk = torch.randn(h_kv, s_k, d, generator=g, dtype=torch.float64, requires_grad=True)
+    tv = torch.randn(h_kv, s_k, d, generator=g, dtype=torch.float64, requires_grad=True)
+    scale = 0.3
+    grp = h_q // h_kv
+    s = scale * tq @ tk.repeat_interleave(grp, 0).transpose(1, 2)
+    o = torch.softmax(s, -1) @ tv.repeat_interleave(grp, 0)
+    o.backward(tdo)
+    q, k, v, do = (t.detach().numpy() for t in (tq, tk, tv, tdo))
+    O, L = A.attention_fwd(q, k, v, scale, causal=False, row_block=16)
+    assert O.shape == (h_q, s_q, d) and L.shape == (h_q, s_q)
+    assert np.abs(O - o.detach().numpy()).max() < 1e-13
+    assert np.abs(L - torch.logsumexp(s, -1).detach().numpy()).max() < 1e-13
+    dq, dk, dv = A.attention_bwd(q, k, v, do, scale, causal=False, row_block=16)
+    assert dk.shape == k.shape and dv.shape == v.shape
+    assert np.abs(dq - tq.grad.numpy()).max() < 1e-12
+    assert np.abs(dk - tk.grad.numpy()).max() < 1e-12
+    assert np.abs(dv - tv.grad.numpy()).max() < 1e-12
+
+
+def test_causal_chunk_then_unmasked_ragged_chunks_merge_to_softmax_over_all_keys():
+    """A causal square chunk followed by unmasked chunks of other sizes, merged: equals torch's
+    softmax over the concatenated keys under the combined mask."""
+    h_q, h_kv, s_q, d, scale = 4, 2, 13, 8, 0.4
+    sizes = [13, 5, 21]
+    g = torch.Generator().manual_seed(5)
+    tq = torch.randn(h_q, s_q, d, generator=g, dtype=torch.float64)
+    ks = [torch.randn(h_kv, n, d, generator=g, dtype=torch.float64) for n in sizes]
+    vs = [torch.randn(h_kv, n, d, generator=g, dtype=torch.float64) for n in sizes]
+    O, L = A.attention_fwd(tq.numpy(), ks[0].numpy(), vs[0].numpy(), scale, causal=True)
+    for k, v in zip(ks[1:], vs[1:]):
+        O, L = A.merge(O, L, *A.attention_fwd(tq.numpy(), k.numpy(), v.numpy(), scale, causal=False))
+    kk = torch.cat(ks, 1).repeat_interleave(2, 0); vv = torch.cat(vs, 1).repeat_interleave(2, 0)
+    s = scale * tq @ kk.transpose(1, 2)
+    mask = torch.zeros(s_q, sum(sizes), dtype=torch.bool)
+    mask[:, :sizes[0]] = torch.triu(torch.ones(s_q, sizes[0], dtype=torch.bool), 1)
+    s = s.masked_fill(mask, float("-inf"))
+    assert np.abs(O - (torch.softmax(s, -1) @ vv).numpy()).max() < 1e-13
+    assert np.abs(L - torch.logsumexp(s, -1).numpy()).max() < 1e-13
+
+
 # ------------------------------------------------- chunk pairs and merging
 @pytest.mark.parametrize("P", range(1, 10))
 def test_merged_pair_partials_equal_monolithic(P):
