@@ -256,21 +256,32 @@ def run_share(w, cfg_index, args, steps, warmup, dev, keep_head=None):
 
 
 def mfma_ceiling(dev):
-    """On-box ceiling of the matrix pipes: a register-resident MFMA stream at the clock the device
-    sustains under that load; median, min and max of several launches (it moves with the clock state)."""
+    """On-box ceilings of the matrix pipes: register-resident MFMA streams at the clock the device
+    sustains under them.  (a) near-constant operands, a few milliseconds: what the pipes do when power
+    is no limit; (b) i.i.d. N(0, 1) bf16 operands (the workload's values), rotating, > 100 ms: the
+    device holds its power limit by lowering the clock, and operands with many toggling bits draw
+    more power per MFMA, so this is the rate an attention kernel on this data could at best reach
+    with every operand already in registers.  Median, min and max of several launches each."""
     import torch
     from paper_2310_03294_amd import binding as B
     out = torch.empty(512 * 256, dtype=torch.float32, device=dev)
-    B.dfa_mfma_probe(out, 4000)
-    vals = []
-    for _ in range(7):
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        e0.record()
-        flop = B.dfa_mfma_probe(out, 20000)
-        e1.record()
-        torch.cuda.synchronize()
-        vals.append(flop / (e0.elapsed_time(e1) * 1e-3) / 1e12)
-    return statistics.median(vals), min(vals), max(vals)
+
+    def rate(launch, reps):
+        launch(True)
+        vals = []
+        for _ in range(reps):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            flop = launch(False)
+            e1.record()
+            torch.cuda.synchronize()
+            vals.append(flop / (e0.elapsed_time(e1) * 1e-3) / 1e12)
+        return statistics.median(vals), min(vals), max(vals)
+
+    plain = rate(lambda warm: B.dfa_mfma_probe(out, 4000 if warm else 20000), 7)
+    ops = torch.randn(1 << 22, generator=torch.Generator(device="cpu").manual_seed(4321)).to(torch.bfloat16).to(dev)
+    data = rate(lambda warm: B.dfa_mfma_probe_data(ops, out, 20000 if warm else 400000), 3)
+    return plain, data
 
 
 def main():
@@ -301,10 +312,13 @@ def main():
     keep = None if args.no_cpu_baseline else 0
     res, share = run_share(w, args.config, args, args.steps, args.warmup, dev, keep_head=keep)
     roofline = res.pop("roofline")
-    ceiling, c_min, c_max = mfma_ceiling(dev)
+    (ceiling, c_min, c_max), (ceil_data, d_min, d_max) = mfma_ceiling(dev)
     roofline["onbox_mfma_ceiling"] = round(ceiling, 1)
     roofline["onbox_mfma_ceiling_range"] = [round(c_min, 1), round(c_max, 1)]
     roofline["frac_of_onbox_ceiling"] = round(roofline["achieved"] / ceiling, 4)
+    roofline["onbox_mfma_ceiling_n01_operands"] = round(ceil_data, 1)
+    roofline["onbox_mfma_ceiling_n01_operands_range"] = [round(d_min, 1), round(d_max, 1)]
+    roofline["frac_of_onbox_ceiling_n01_operands"] = round(roofline["achieved"] / ceil_data, 4)
 
     out = {
         "metric": "causal-adjusted attention TFLOP/s fwd+bwd per worker share; % of bf16 MFMA peak",
@@ -315,6 +329,7 @@ def main():
         "config": {"workload": res["workload"], "n_total": w.n_total, "P": w.p, "chunk": w.chunk},
         "pct_of_bf16_peak": res["pct_of_bf16_peak"],
         "pct_of_onbox_mfma_ceiling": round(100.0 * res["value"] / ceiling, 2),
+        "pct_of_onbox_mfma_ceiling_n01_operands": round(100.0 * res["value"] / ceil_data, 2),
         "flop_per_step": res["flop_per_step"],
         "roofline": roofline,
     }

@@ -125,8 +125,8 @@ int dfa_delta(const dfa_shape* sh, const void* o, const void* dO, float* delta, 
 
 /*
  * dfa_chunk_bwd - gradient contributions of one (query chunk, key/value chunk) pair
- * without re-running the forward (Section 3.3, Appendix A "the backward only needs the
- * logsumexp stored in the forward").  With P_ij = exp(scale q_i.k_j - lse_i) for
+ * without re-running the forward (Section 3.3; Appendix A: of the forward's results the backward
+ * uses the saved logsumexp alone).  With P_ij = exp(scale q_i.k_j - lse_i) for
  * visible keys (0 otherwise), dP_ij = dO_i.v_j and dS_ij = P_ij (dP_ij - D_i):
  *   dq_i (+)= scale sum_j dS_ij k_j;  dk_j (+)= scale sum_i dS_ij q_i;  dv_j (+)= sum_i P_ij dO_i
  * where dk, dv also sum over the query heads that share the key/value head.
@@ -190,6 +190,19 @@ int dfa_schedule_window(int32_t P, int32_t worker_id, int32_t window_chunks, dfa
  * values of no meaning; `flop`: HOST pointer receiving the FLOP count of the launch (may be NULL).
  * Errors: DFA_ERR_NULL (out), DFA_ERR_ARG (iters < 1 or n_out too small), DFA_ERR_HIP. */
 int dfa_mfma_probe(float* out, int64_t n_out, int32_t iters, double* flop, void* stream);
+
+/* Measurement aid (no part of the method): the same register-resident MFMA stream fed with operand
+ * VALUES of the caller's choosing.  Every wavefront loads eight A and eight B operands from
+ * `operands` (DEVICE, bf16 values, 16-byte aligned, operand_bytes >= 1 MiB; a power-of-two prefix of
+ * it is used) and rotates through them, 8 * iters MFMAs per wavefront.  The device keeps its power
+ * limit by lowering the clock, and how much power an MFMA draws depends on how many operand bits
+ * toggle: with i.i.d. N(0,1) operands (the workload's values) the sustained rate is what the
+ * attention kernels can at best reach, well below what the plain probe's near-constant operands
+ * give.  Run it for 100 ms or more (iters ~ 400000) so that the clock has settled.
+ * `out`, `flop`, `stream` and errors as for dfa_mfma_probe; DFA_ERR_SHAPE for a misaligned and
+ * DFA_ERR_ARG for a too small operand buffer. */
+int dfa_mfma_probe_data(const void* operands, int64_t operand_bytes, float* out, int64_t n_out,
+                        int32_t iters, double* flop, void* stream);
 
 /* Human-readable name of a dfa_status (static storage, host). */
 const char* dfa_status_str(int status);

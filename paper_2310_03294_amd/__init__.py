@@ -13,6 +13,7 @@ from .binding import (  # noqa: F401
     dfa_delta,
     dfa_merge,
     dfa_mfma_probe,
+    dfa_mfma_probe_data,
     dfa_schedule,
     dfa_status_str,
     dfa_version,

@@ -52,7 +52,8 @@ class DfaStep(ctypes.Structure):
 Step = collections.namedtuple("Step", "t kind q_chunk kv_chunk send_to recv_from")
 
 EXPORTS = ("dfa_chunk_fwd", "dfa_chunk_fwd_acc", "dfa_merge", "dfa_delta", "dfa_chunk_bwd", "dfa_schedule",
-           "dfa_schedule_mode", "dfa_schedule_window", "dfa_mfma_probe", "dfa_status_str", "dfa_version")
+           "dfa_schedule_mode", "dfa_schedule_window", "dfa_mfma_probe", "dfa_mfma_probe_data", "dfa_status_str",
+           "dfa_version")
 
 
 def lib_path() -> str:
@@ -81,6 +82,8 @@ def load_library():
     lib.dfa_schedule_window.argtypes = [i32, i32, i32, ctypes.POINTER(DfaStep), i32]
     lib.dfa_mfma_probe.argtypes = [ctypes.c_void_p, ctypes.c_int64, i32, ctypes.POINTER(ctypes.c_double),
                                    ctypes.c_void_p]
+    lib.dfa_mfma_probe_data.argtypes = [ctypes.c_void_p, ctypes.c_int64, ctypes.c_void_p, ctypes.c_int64, i32,
+                                        ctypes.POINTER(ctypes.c_double), ctypes.c_void_p]
     lib.dfa_status_str.argtypes = [ctypes.c_int]
     lib.dfa_status_str.restype = ctypes.c_char_p
     lib.dfa_version.argtypes = []
@@ -242,6 +245,18 @@ def dfa_mfma_probe(out, iters: int, stream=None) -> float:
     flop = ctypes.c_double(0.0)
     _check(lib.dfa_mfma_probe(out.data_ptr(), out.numel(), int(iters), ctypes.byref(flop), _stream(stream)),
            "dfa_mfma_probe")
+    return flop.value
+
+
+def dfa_mfma_probe_data(operands, out, iters: int, stream=None) -> float:
+    """The MFMA stream fed with the values of `operands` (a contiguous bf16 device tensor of at least
+    1 MiB); returns its FLOP count."""
+    lib = load_library()
+    if operands.dtype != torch.bfloat16 or not operands.is_contiguous():
+        raise TypeError("operands must be a contiguous bf16 tensor")
+    flop = ctypes.c_double(0.0)
+    _check(lib.dfa_mfma_probe_data(operands.data_ptr(), operands.numel() * 2, out.data_ptr(), out.numel(),
+                                   int(iters), ctypes.byref(flop), _stream(stream)), "dfa_mfma_probe_data")
     return flop.value
 
 

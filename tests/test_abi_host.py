@@ -70,6 +70,17 @@ def test_mfma_probe_rejects_bad_arguments_before_any_launch(lib):
     assert lib.dfa_mfma_probe(ctypes.c_void_p(256), 1000, 10, ctypes.byref(flop), None) == -4
 
 
+def test_mfma_probe_data_rejects_bad_arguments_before_any_launch(lib):
+    flop = ctypes.c_double(0)
+    ok = ctypes.c_void_p(4096)
+    assert lib.dfa_mfma_probe_data(None, 1 << 20, ok, 1 << 20, 10, ctypes.byref(flop), None) == -1
+    assert lib.dfa_mfma_probe_data(ok, 1 << 20, None, 1 << 20, 10, ctypes.byref(flop), None) == -1
+    assert lib.dfa_mfma_probe_data(ok, (1 << 20) - 16, ok, 1 << 20, 10, ctypes.byref(flop), None) == -4
+    assert lib.dfa_mfma_probe_data(ok, 1 << 20, ok, 1 << 20, 0, ctypes.byref(flop), None) == -4
+    assert lib.dfa_mfma_probe_data(ok, 1 << 20, ok, 1000, 10, ctypes.byref(flop), None) == -4
+    assert lib.dfa_mfma_probe_data(ctypes.c_void_p(4100), 1 << 20, ok, 1 << 20, 10, ctypes.byref(flop), None) == -2
+
+
 def test_schedule_errors_and_cap(lib):
     buf = (B.DfaStep * 2)()
     assert lib.dfa_schedule(0, 0, buf, 2) == -4

@@ -338,6 +338,15 @@ def test_mfma_probe_runs_and_counts_its_flop():
     assert bool(torch.isfinite(out).all())
 
 
+def test_mfma_probe_data_runs_and_counts_its_flop():
+    ops = torch.randn(1 << 20, generator=torch.Generator().manual_seed(1)).to(torch.bfloat16).to(dev())
+    out = torch.empty(512 * 256, dtype=torch.float32, device=dev())
+    flop = dfa.dfa_mfma_probe_data(ops, out, 100)
+    torch.cuda.synchronize()
+    assert flop == 2.0 * 32 * 32 * 16 * 8 * 100 * 2048
+    assert bool(torch.isfinite(out).all())
+
+
 @pytest.mark.parametrize("shape", [(4, 2, 333, 451, False, 12), (8, 2, 257, 257, True, 12), (32, 8, 1024, 2048, False, 6)])
 def test_results_repeat_bit_for_bit(shape):
     """The kernels use no atomics and a fixed summation order, so repeated calls must agree bit for
