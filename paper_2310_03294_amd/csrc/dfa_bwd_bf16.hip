@@ -454,11 +454,17 @@ __global__ void __launch_bounds__(NT, 2) k_bwd_dkdv_bf16(BwdParams p) {
 // ============================================================================================
 namespace qs {
 
-constexpr int BM = 128;     // query rows per workgroup
 constexpr int BN = 64;      // key rows per LDS tile
 constexpr int TILE_BYTES = BN * kRowBytes;
 
-__global__ void __launch_bounds__(NTHREADS, 2) k_bwd_dq_bf16(BwdParams p) {
+// NW wavefronts of 32 query rows each per workgroup, two wavefronts per SIMD either way: NW = 4 (128
+// rows, two workgroups per CU, scheduled independently of each other) or NW = 8 (256 rows, one
+// workgroup per CU: every K/V tile copy and every barrier serve twice the rows; measured 2-3 %
+// faster on long chunks, where the copies are what the second independent workgroup used to hide, and
+// no faster on short ones and on the causal diagonal pair, which keep the 128-row form).
+template <int NW>
+__global__ void __launch_bounds__(NW * 64, NW == 4 ? 2 : 1) k_bwd_dq_bf16(BwdParams p) {
+  constexpr int BM = NW * 32;     // query rows per workgroup
   extern __shared__ __align__(16) char smem[];   // two (K tile, V tile) buffers
 
   const int bid = blockIdx.x;
@@ -482,7 +488,10 @@ __global__ void __launch_bounds__(NTHREADS, 2) k_bwd_dq_bf16(BwdParams p) {
   const char* kg = reinterpret_cast<const char*>(p.k + kh * p.kv_sh);
   const char* vg = reinterpret_cast<const char*>(p.v + kh * p.kv_sh);
   const uint32_t kv_rowbytes = static_cast<uint32_t>(p.kv_ss) * 2;
-  const TileLane tl = tile_lane(wave, lane, kv_rowbytes);
+  // Tile copies: with 4 wavefronts each moves its quarter of the K tile and of the V tile; with 8,
+  // wavefronts 0-3 move the K tile and 4-7 the V tile.
+  const int cw = wave & 3;
+  const TileLane tl = tile_lane(cw, lane, kv_rowbytes);
 
   // Q^T and dO^T operands: lane holds row qrow, columns 16 ks + 8 hh .. +7; lse' and D of that row
   bf16x8 qB[8], gB[8];
@@ -521,8 +530,8 @@ __global__ void __launch_bounds__(NTHREADS, 2) k_bwd_dq_bf16(BwdParams p) {
 
   // K/V tiles go from global memory straight into LDS; key rows past s_k are clamped to the last
   // row and masked below.  Tile t + 1 is on its way while tile t is computed on.
-  tile_dma(kg, kv_rowbytes, 0, p.s_k - 1, tl, smem, wave, lane);
-  tile_dma(vg, kv_rowbytes, 0, p.s_k - 1, tl, smem + TILE_BYTES, wave, lane);
+  if (NW == 4 || wave < 4) tile_dma(kg, kv_rowbytes, 0, p.s_k - 1, tl, smem, cw, lane);
+  if (NW == 4 || wave >= 4) tile_dma(vg, kv_rowbytes, 0, p.s_k - 1, tl, smem + TILE_BYTES, cw, lane);
   lds_dma_wait();
   __syncthreads();
 
@@ -536,14 +545,21 @@ __global__ void __launch_bounds__(NTHREADS, 2) k_bwd_dq_bf16(BwdParams p) {
     // branches around the copies.
     const int kn0 = it + 1 < ntiles ? k0 + BN : k0;
     const char* Kn = smem + ((it + 1) & 1) * 2 * TILE_BYTES;
-    const TileCopy ck = tile_copy_plan(kg, kv_rowbytes, kn0, p.s_k - 1, tl, Kn, wave, lane);
-    const TileCopy cv = tile_copy_plan(vg, kv_rowbytes, kn0, p.s_k - 1, tl, Kn + TILE_BYTES, wave, lane);
+    // ck: the pieces issued under the first 32 keys, cv: those under the second 32 (NW == 4: K and V;
+    // NW == 8: this wavefront's one tile under the first, nothing under the second)
+    const bool v_wave = NW == 8 && wave >= 4;
+    const TileCopy ck = tile_copy_plan(v_wave ? vg : kg, kv_rowbytes, kn0, p.s_k - 1, tl,
+                                       v_wave ? Kn + TILE_BYTES : Kn, cw, lane);
+    const TileCopy cv = tile_copy_plan(vg, kv_rowbytes, kn0, p.s_k - 1, tl, Kn + TILE_BYTES, cw, lane);
 
     const bool active = !(p.causal && k0 > q0w + 31);
     if (!active) {      // nothing to compute for this wavefront's rows: only its share of the copies
       tile_copy_piece<0>(ck); tile_copy_piece<1>(ck); tile_copy_piece<2>(ck); tile_copy_piece<3>(ck);
-      tile_copy_piece<0>(cv); tile_copy_piece<1>(cv); tile_copy_piece<2>(cv); tile_copy_piece<3>(cv);
-      if (wave == 0) { tile_copy_piece<4>(ck); tile_copy_piece<4>(cv); }
+      if (cw == 0) tile_copy_piece<4>(ck);
+      if (NW == 4) {
+        tile_copy_piece<0>(cv); tile_copy_piece<1>(cv); tile_copy_piece<2>(cv); tile_copy_piece<3>(cv);
+        if (cw == 0) tile_copy_piece<4>(cv);
+      }
     }
     if (active) {
       const bool need_mask = (k0 + BN > p.s_k) || (p.causal && k0 + BN - 1 > q0w);
@@ -565,7 +581,7 @@ __global__ void __launch_bounds__(NTHREADS, 2) k_bwd_dq_bf16(BwdParams p) {
         for (int ks = 0; ks < 8; ++ks) {
           s = mfma32(ka[ks & 3], qB[ks], s);
           dp = mfma32(va[ks & 3], gB[ks], ks == 0 ? negD : dp);      // the chain starts from -D
-          {   // one piece of the next tiles every other step: K under the first 32 keys, V under the second
+          if (NW == 4 || nb == 0) {   // one piece of the next tiles every other step
             const TileCopy& c = nb == 0 ? ck : cv;
             if (ks == 0) tile_copy_piece<0>(c);
             if (ks == 2) tile_copy_piece<1>(c);
@@ -592,7 +608,7 @@ __global__ void __launch_bounds__(NTHREADS, 2) k_bwd_dq_bf16(BwdParams p) {
             if (kvi >= p.s_k || (p.causal && kvi > qrow)) dp[j] = 0.f;
           }
         }
-        if (wave == 0) tile_copy_piece<4>(nb == 0 ? ck : cv);
+        if (cw == 0 && (NW == 4 || nb == 0)) tile_copy_piece<4>(nb == 0 ? ck : cv);
         // dQ^T += K^T dS^T: 2 contraction steps of 16 keys, 4 blocks of 32 columns
         bf16x8 sb[2], gk[2];
         sb[0] = pack8(dp, 0); sb[1] = pack8(dp, 8);
@@ -673,21 +689,28 @@ int launch_bwd_bf16(const dfa_shape& sh, const void* q, const void* k, const voi
   }
   if (dq) {  // dQ
     BwdParams b = p;
-    b.ntile = (sh.s_q + qs::BM - 1) / qs::BM;
-    const int64_t total = static_cast<int64_t>(b.ntile) * sh.h_q;
-    if (total > (1 << 30)) return DFA_ERR_SHAPE;
-    b.total = static_cast<int>(total);
-    b.per_xcd = (b.total + 7) / 8;
     const size_t smem = 4 * qs::TILE_BYTES;
     static std::once_flag once;
     static int attr_rc = DFA_OK;
     std::call_once(once, [smem] {
-      attr_rc = hip_status(hipFuncSetAttribute(reinterpret_cast<const void*>(qs::k_bwd_dq_bf16),
-                                               hipFuncAttributeMaxDynamicSharedMemorySize,
-                                               static_cast<int>(smem)));
+      for (const void* f : {reinterpret_cast<const void*>(qs::k_bwd_dq_bf16<4>),
+                            reinterpret_cast<const void*>(qs::k_bwd_dq_bf16<8>)}) {
+        const int rc = hip_status(hipFuncSetAttribute(f, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                                      static_cast<int>(smem)));
+        if (rc) attr_rc = rc;
+      }
     });
     if (attr_rc) return attr_rc;
-    qs::k_bwd_dq_bf16<<<b.per_xcd * 8, NTHREADS, smem, st>>>(b);
+    // 256-row workgroups for long unmasked chunks (at least four of them per CU), 128 rows otherwise
+    const bool wide = !sh.causal && static_cast<int64_t>(sh.h_q) * ((sh.s_q + 255) / 256) >= 1024;
+    const int bm = wide ? 256 : 128;
+    b.ntile = (sh.s_q + bm - 1) / bm;
+    const int64_t total = static_cast<int64_t>(b.ntile) * sh.h_q;
+    if (total > (1 << 30)) return DFA_ERR_SHAPE;
+    b.total = static_cast<int>(total);
+    b.per_xcd = (b.total + 7) / 8;
+    if (wide) qs::k_bwd_dq_bf16<8><<<b.per_xcd * 8, 512, smem, st>>>(b);
+    else qs::k_bwd_dq_bf16<4><<<b.per_xcd * 8, 256, smem, st>>>(b);
   }
   return last_launch_status();
 }

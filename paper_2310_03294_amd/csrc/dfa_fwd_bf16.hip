@@ -12,6 +12,7 @@
 // ds_read_b64_tr_b16.  The causal mask is applied only on tiles that straddle the
 // diagonal; tiles above it are skipped.
 #include <mutex>
+#include <type_traits>
 
 #include "dfa_internal.h"
 #include "dfa_mfma.h"
@@ -401,7 +402,10 @@ __global__ void __launch_bounds__(NT, 1) k_fwd_bf16(FwdParams p) {
       }
       if (active) {
         f32x16 s0, s1;
-        {
+        // S^T = K Q^T of the tile's two 32-key blocks.  COPIES: this wavefront's pieces of the next
+        // tile's copy go out between the MFMAs (false when the products are done a second time).
+        auto s_products = [&](auto copies) {
+          constexpr bool COPIES = decltype(copies)::value;
           bf16x8 x0[4], x1[4];
           f32x16 zero;
 #pragma unroll
@@ -421,49 +425,76 @@ __global__ void __launch_bounds__(NT, 1) k_fwd_bf16(FwdParams p) {
             }
             s0 = mfma32(x0[ks & 3], qreg[ks], ks == 0 ? zero : s0);
             s1 = mfma32(x1[ks & 3], qreg[ks], ks == 0 ? zero : s1);
-            if (ks == 0) tile_copy_piece<0>(cn);
-            if (ks == 2) tile_copy_piece<1>(cn);
-            if (ks == 4) tile_copy_piece<2>(cn);
-            if (ks == 6) tile_copy_piece<3>(cn);
+            if (COPIES) {
+              if (ks == 0) tile_copy_piece<0>(cn);
+              if (ks == 2) tile_copy_piece<1>(cn);
+              if (ks == 4) tile_copy_piece<2>(cn);
+              if (ks == 6) tile_copy_piece<3>(cn);
+            }
             DFA_SCHED_FENCE();
           }
           __builtin_amdgcn_s_setprio(0);
-          if ((wave & 3) == 0) tile_copy_piece<4>(cn);
-        }
-        if ((k0 + BN > p.s_k) || (p.causal && k0 + BN - 1 > q0w)) {
+          if (COPIES && (wave & 3) == 0) tile_copy_piece<4>(cn);
+          if ((k0 + BN > p.s_k) || (p.causal && k0 + BN - 1 > q0w)) {
 #pragma unroll
-          for (int j = 0; j < 16; ++j) {
-            const int kvi = k0 + (j >> 2) * 8 + hh * 4 + (j & 3);
-            if (kvi >= p.s_k || (p.causal && kvi > qrow)) s0[j] = -INFINITY;
-            if (kvi + 32 >= p.s_k || (p.causal && kvi + 32 > qrow)) s1[j] = -INFINITY;
+            for (int j = 0; j < 16; ++j) {
+              const int kvi = k0 + (j >> 2) * 8 + hh * 4 + (j & 3);
+              if (kvi >= p.s_k || (p.causal && kvi > qrow)) s0[j] = -INFINITY;
+              if (kvi + 32 >= p.s_k || (p.causal && kvi + 32 > qrow)) s1[j] = -INFINITY;
+            }
           }
-        }
-        // Online softmax of the 64-key tile (exp2 domain) with a lazy running maximum: the
-        // reference only moves when some row's tile maximum exceeds it by more than 2^8 (or on
-        // the first tile); until then exponentials against the stale maximum stay below 2^8 and
-        // O needs no rescaling.  The final division by the row sum removes the reference.
-        float mx = fmaxf(s0[0], s1[0]);
+        };
+        // Moves the reference maximum up to the tile's row maxima; returns the factor by which what
+        // has been accumulated against the old reference shrinks.
+        auto new_reference = [&]() {
+          float mx = fmaxf(s0[0], s1[0]);
 #pragma unroll
-        for (int j = 1; j < 16; ++j) mx = fmaxf(fmaxf(mx, s0[j]), s1[j]);
-        float alpha = 1.f;
-        if (__any((mx - m_run) * c2 > 8.f)) {          // -inf reference (first tile) also lands here
+          for (int j = 1; j < 16; ++j) mx = fmaxf(fmaxf(mx, s0[j]), s1[j]);
           mx = fmaxf(mx, __shfl_xor(mx, 32));
           const float m_new = fmaxf(m_run, mx);
           const float mc_new = (m_new == -INFINITY) ? 0.f : m_new * c2;
-          alpha = __builtin_amdgcn_exp2f(m_run * c2 - mc_new);
+          const float a = __builtin_amdgcn_exp2f(m_run * c2 - mc_new);
           m_run = m_new;
-          l_run *= alpha;
-        }
-        const float mc = (m_run == -INFINITY) ? 0.f : m_run * c2;
-        float sum = 0.f;
+          l_run *= a;
+          return a;
+        };
+        // P^T = exp2(S^T c - reference) rounded to bf16, and this lane's half of the tile's row sum, taken
+        // over the ROUNDED values (v_dot2c_f32_bf16 against a pair of ones: one instruction per two
+        // scores), so that the sum that normalises O is the sum of exactly the weights that multiply V.
+        bf16x8 p0, p1, p2, p3;
+        auto exponentials = [&]() {
+          const float mc = (m_run == -INFINITY) ? 0.f : m_run * c2;
 #pragma unroll
-        for (int j = 0; j < 16; ++j) {
-          s0[j] = __builtin_amdgcn_exp2f(fmaf(s0[j], c2, -mc));
-          s1[j] = __builtin_amdgcn_exp2f(fmaf(s1[j], c2, -mc));
-          sum += s0[j] + s1[j];
+          for (int j = 0; j < 16; ++j) {
+            s0[j] = __builtin_amdgcn_exp2f(fmaf(s0[j], c2, -mc));
+            s1[j] = __builtin_amdgcn_exp2f(fmaf(s1[j], c2, -mc));
+          }
+          p0 = pack8(s0, 0); p1 = pack8(s0, 8); p2 = pack8(s1, 0); p3 = pack8(s1, 8);
+          // two independent chains, so that the adds do not wait for one another
+          const float sa = sum8(p2, sum8(p0, 0.f)), sb = sum8(p3, sum8(p1, 0.f));
+          const float sum = sa + sb;
+          return sum;
+        };
+        // Online softmax of the 64-key tile (exp2 domain) against a reference maximum that is only
+        // moved when it has to be.  A tile is first exponentiated against the reference as it stands,
+        // without looking for its maximum: as long as no score lies more than 2^14 above the
+        // reference, the exponentials are harmless in fp32 / bf16, O needs no rescaling, and the final
+        // division by the row sum removes the reference.  The reference is derived from the scores
+        // themselves (row maximum, one exchange between the two half rows) on a row's first tile -
+        // so the largest weight seen is at least 1 and later tiles cannot underflow the row sum - and
+        // again when a tile's half-row sum shows a score far above it (or is no number): that tile's
+        // products are then done once more and the tile is redone with the moved reference.
+        float alpha = 1.f;
+        s_products(std::true_type{});
+        const bool fresh = __any(m_run == -INFINITY);
+        if (fresh) alpha = new_reference();
+        float sum = exponentials();
+        if (!fresh && __any(!(sum <= 16384.f))) {
+          s_products(std::false_type{});
+          alpha = new_reference();
+          sum = exponentials();
         }
         l_run += sum;
-        const bf16x8 p0 = pack8(s0, 0), p1 = pack8(s0, 8), p2 = pack8(s1, 0), p3 = pack8(s1, 8);
         // hand P^T and the factor to the PV wavefront: lane-private, any layout will do
         char* px = smem + OFF_PX + (it & 1) * PX_BYTES + wave * 4096 + lane * 16;
         *reinterpret_cast<bf16x8*>(px) = p0;

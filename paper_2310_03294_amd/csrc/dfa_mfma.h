@@ -25,6 +25,7 @@ namespace dfa {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 typedef short s16x4 __attribute__((ext_vector_type(4)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
@@ -242,6 +243,18 @@ __device__ __forceinline__ void tile_copy_piece(const TileCopy& c) {
 }
 
 __device__ __forceinline__ void lds_dma_wait() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
+
+// acc + the sum of the eight bf16 values of v, in fp32: v_dot2c_f32_bf16 against a pair of ones adds
+// two of them per instruction.
+__device__ __forceinline__ float sum8(bf16x8 v, float acc) {
+  bf16x2 ones;
+  ones[0] = static_cast<__bf16>(1.f); ones[1] = ones[0];
+  acc = __builtin_amdgcn_fdot2_f32_bf16(__builtin_shufflevector(v, v, 0, 1), ones, acc, false);
+  acc = __builtin_amdgcn_fdot2_f32_bf16(__builtin_shufflevector(v, v, 2, 3), ones, acc, false);
+  acc = __builtin_amdgcn_fdot2_f32_bf16(__builtin_shufflevector(v, v, 4, 5), ones, acc, false);
+  acc = __builtin_amdgcn_fdot2_f32_bf16(__builtin_shufflevector(v, v, 6, 7), ones, acc, false);
+  return acc;
+}
 
 __device__ __forceinline__ bf16x8 pack8(const f32x16& v, int first) {
   bf16x8 r;
