@@ -50,6 +50,9 @@ def parse():
     ap.add_argument("--schedule", choices=("balanced", "ring"), default="balanced",
                     help="balanced: the load-balanced schedule (the metric's workload); ring: the plain ring "
                          "schedule, where worker P-1 computes all P of its pairs itself (ablation)")
+    ap.add_argument("--zero-operand-steps", type=int, default=3,
+                    help="after the timed region, time this many steps of the same share on all-zero operands "
+                         "(evidence of the power limit; 0 = skip)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also launch one plain elementwise kernel that reads 1 GiB and writes 1 GiB, "
                          "the known-size reference for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE readings")
@@ -142,8 +145,10 @@ def cpu_baseline(w, worker, share, mode):
                       f"{n - lo} keys ({nnz} unmasked scores): rows_fwd + rows_dq + cols_dkdv, fp64 numpy, {dt:.1f} s"}
 
 
-def run_share(w, cfg_index, args, steps, warmup, dev, keep_head=None):
-    """Times `steps` passes of worker P-1's share of workload w.  Returns (result dict, Share)."""
+def run_share(w, cfg_index, args, steps, warmup, dev, keep_head=None, zero_steps=0):
+    """Times `steps` passes of worker P-1's share of workload w.  Returns (result dict, Share).
+    zero_steps > 0: afterwards the inputs are zeroed and that many more steps are timed (the Share's
+    device tensors are then no longer the workload)."""
     import torch
     import paper_2310_03294_amd as dfa
     from paper_2310_03294_amd import driver, binding as B
@@ -244,6 +249,23 @@ def run_share(w, cfg_index, args, steps, warmup, dev, keep_head=None):
                     f"forward (k_fwd_bf16 x{len(pairs)} + k_merge x{len(remote)})": {
                         "ms_per_step": round(fw_ms / fw_n, 4), "tflops": round(fw_fl / (fw_ms * 1e-3) / 1e12, 2),
                         "share_of_step": round(fw_ms / fw_n / ms, 3)}}}
+    zero_ops = None
+    if zero_steps > 0:
+        # The same launches on all-zero operands (wrong for the method, same instruction streams):
+        # what these kernels do when operand values cost no power.  After the timed region.
+        for t in (Q, K, V, dO):
+            t.zero_()
+        step(False)
+        torch.cuda.synchronize()
+        z0 = time.perf_counter()
+        for _ in range(zero_steps):
+            step(False)
+        torch.cuda.synchronize()
+        zms = (time.perf_counter() - z0) * 1e3 / zero_steps
+        zero_ops = {"value": round(flops_step / (zms * 1e-3) / 1e12, 2), "unit": "TFLOP/s", "ms_per_step": round(zms, 4),
+                    "steps": zero_steps,
+                    "note": "same share, same launches, every operand zero: the device holds its power limit by "
+                            "lowering the clock, and N(0,1) operands draw far more power per MFMA than zeros"}
     res = {"value": round(tflops, 2), "ms_per_step": round(ms, 4),
            "ms_per_step_median": round(statistics.median(per_step), 4), "ms_per_step_min": round(min(per_step), 4),
            "steps": steps, "warmup": warmup, "flop_per_step": flops_step,
@@ -251,6 +273,8 @@ def run_share(w, cfg_index, args, steps, warmup, dev, keep_head=None):
            "workload": f"{w.name}: worker {worker} share ({args.schedule} schedule), {len(pairs)} pairs fwd+bwd + "
                        f"{len(remote)} remote merges, H={w.h_q}/{w.h_kv} d={w.d} C={c}",
            "roofline": roofline}
+    if zero_ops is not None:
+        res["zero_operands"] = zero_ops
     del bufs, remote, prefetch
     return res, share
 
@@ -310,7 +334,8 @@ def main():
         del src, dst
 
     keep = None if args.no_cpu_baseline else 0
-    res, share = run_share(w, args.config, args, args.steps, args.warmup, dev, keep_head=keep)
+    res, share = run_share(w, args.config, args, args.steps, args.warmup, dev, keep_head=keep,
+                           zero_steps=args.zero_operand_steps)
     roofline = res.pop("roofline")
     (ceiling, c_min, c_max), (ceil_data, d_min, d_max) = mfma_ceiling(dev)
     roofline["onbox_mfma_ceiling"] = round(ceiling, 1)
@@ -333,6 +358,8 @@ def main():
         "flop_per_step": res["flop_per_step"],
         "roofline": roofline,
     }
+    if "zero_operands" in res:
+        out["zero_operands"] = res["zero_operands"]
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(w, w.p - 1, share, args.schedule)
     del share
