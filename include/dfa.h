@@ -44,7 +44,7 @@ typedef enum {
   DFA_ERR_SHAPE = -2,     /* sizes / strides / alignment the kernels cannot take */
   DFA_ERR_DTYPE = -3,     /* unknown or unsupported dtype combination */
   DFA_ERR_ARG = -4,       /* inconsistent arguments (e.g. causal with s_q != s_k) */
-  DFA_ERR_WORKSPACE = -5, /* reserved: no entry point takes a workspace yet */
+  /* -5 is not used: no entry point takes a workspace (every buffer is an input or an output) */
   DFA_ERR_HIP = -6        /* the HIP runtime refused a launch */
 } dfa_status;
 

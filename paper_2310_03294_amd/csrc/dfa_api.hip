@@ -39,7 +39,6 @@ extern "C" const char* dfa_status_str(int s) {
     case DFA_ERR_SHAPE: return "DFA_ERR_SHAPE: unsupported size, stride or alignment";
     case DFA_ERR_DTYPE: return "DFA_ERR_DTYPE: unsupported dtype";
     case DFA_ERR_ARG: return "DFA_ERR_ARG: inconsistent arguments";
-    case DFA_ERR_WORKSPACE: return "DFA_ERR_WORKSPACE: workspace too small";
     case DFA_ERR_HIP: return "DFA_ERR_HIP: HIP runtime error";
     default: return "unknown dfa_status";
   }
