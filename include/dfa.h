@@ -20,7 +20,8 @@
  *    head and sequence strides are given in ELEMENTS in dfa_shape, so a chunk can be
  *    a slice of a full-sequence tensor.  Base pointers of [heads, sequence, d] tensors must be
  *    16-byte aligned and their strides multiples of 8 elements; lse / delta vectors
- *    need only float alignment and a head stride >= s_q.  One head's slice of a chunk must
+ *    need only float alignment and a head stride >= s_q.  Head strides are at most 2^40
+ *    elements.  One head's slice of a chunk must
  *    span less than 2 GiB counted in fp32 (rows * sequence stride * 4 < 2^31, DFA_ERR_SHAPE
  *    otherwise): the kernels address it with 32-bit byte offsets.
  *  - Outputs must not overlap inputs (dfa_merge's documented in-place operand aside).

@@ -24,11 +24,16 @@ int check_common(const dfa_shape* sh) {
 
 bool stride_ok(int64_t sh_, int64_t ss, int d, int rows) {
   if (ss < d || !mult8(ss) || !mult8(sh_)) return false;
-  if (sh_ < 0) return false;
-  // the kernels address one head's slice of a chunk with 32-bit byte offsets (fp32 at most)
-  if (static_cast<int64_t>(rows) * ss * 4 >= (int64_t{1} << 31)) return false;
+  // head offsets are formed in 64 bits from at most 65535 heads: keep them far from overflow
+  if (sh_ < 0 || sh_ > (int64_t{1} << 40)) return false;
+  // the kernels address one head's slice of a chunk with 32-bit byte offsets (fp32 at most):
+  // rows * ss * 4 < 2^31, compared without forming a product that could overflow
+  if (rows > 0 && ss > ((int64_t{1} << 29) - 1) / rows) return false;
   return true;
 }
+
+// head stride of an [heads, rows] fp32 vector (lse, D)
+bool row_stride_ok(int64_t sh_, int rows) { return sh_ >= rows && sh_ <= (int64_t{1} << 40); }
 
 }  // namespace
 
@@ -58,7 +63,7 @@ int chunk_fwd(const dfa_shape* sh, const void* q, const void* k, const void* v,
       !stride_ok(sh->kv_stride_h, sh->kv_stride_s, sh->d, sh->s_k) ||
       !stride_ok(sh->o_stride_h, sh->o_stride_s, sh->d, sh->s_q))
     return DFA_ERR_SHAPE;
-  if (sh->lse_stride_h < sh->s_q) return DFA_ERR_SHAPE;
+  if (!row_stride_ok(sh->lse_stride_h, sh->s_q)) return DFA_ERR_SHAPE;
   hipStream_t st = static_cast<hipStream_t>(stream);
   if (sh->s_q == 0) return DFA_OK;
   if (sh->s_k == 0) return accumulate ? DFA_OK : dfa::launch_fill_empty_fwd(*sh, o, lse, st);
@@ -90,7 +95,7 @@ extern "C" int dfa_merge(const dfa_merge_desc* md, void* o_a, float* lse_a,
   if (!stride_ok(md->a_stride_h, md->a_stride_s, md->d, md->rows) ||
       !stride_ok(md->b_stride_h, md->b_stride_s, md->d, md->rows))
     return DFA_ERR_SHAPE;
-  if (md->lse_a_stride_h < md->rows || md->lse_b_stride_h < md->rows) return DFA_ERR_SHAPE;
+  if (!row_stride_ok(md->lse_a_stride_h, md->rows) || !row_stride_ok(md->lse_b_stride_h, md->rows)) return DFA_ERR_SHAPE;
   if (o_a == o_b || lse_a == lse_b) return DFA_ERR_ARG;
   if (md->rows == 0 || md->heads == 0) return DFA_OK;
   return dfa::launch_merge(*md, o_a, lse_a, o_b, lse_b, static_cast<hipStream_t>(stream));
@@ -104,7 +109,7 @@ extern "C" int dfa_delta(const dfa_shape* sh, const void* o, const void* dO, flo
   if (!stride_ok(sh->q_stride_h, sh->q_stride_s, sh->d, sh->s_q) ||
       !stride_ok(sh->o_stride_h, sh->o_stride_s, sh->d, sh->s_q))
     return DFA_ERR_SHAPE;
-  if (sh->lse_stride_h < sh->s_q) return DFA_ERR_SHAPE;
+  if (!row_stride_ok(sh->lse_stride_h, sh->s_q)) return DFA_ERR_SHAPE;
   if (sh->s_q == 0) return DFA_OK;
   return dfa::launch_delta(*sh, o, dO, delta, static_cast<hipStream_t>(stream));
 }
@@ -126,7 +131,7 @@ extern "C" int dfa_chunk_bwd(const dfa_shape* sh, const void* q, const void* k, 
       !stride_ok(sh->dq_stride_h, sh->dq_stride_s, sh->d, sh->s_q) ||
       !stride_ok(sh->dkv_stride_h, sh->dkv_stride_s, sh->d, sh->s_k))
     return DFA_ERR_SHAPE;
-  if (sh->lse_stride_h < sh->s_q) return DFA_ERR_SHAPE;
+  if (!row_stride_ok(sh->lse_stride_h, sh->s_q)) return DFA_ERR_SHAPE;
   hipStream_t st = static_cast<hipStream_t>(stream);
   if (sh->s_q == 0 || sh->s_k == 0) {
     // nothing flows through an empty pair; honour "overwrite" semantics
